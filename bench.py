@@ -1,0 +1,235 @@
+#!/usr/bin/env python3
+"""Benchmark of the five streaming vector kernels (Copy, Mul/scale, Add, Triad, Dot;
+Table 1 of the paper) on one MI355X.
+
+A step is one pass copy -> scale -> add -> triad -> dot over the three resident
+arrays of one synthetic workload, every kernel launched through the C ABI on one
+HIP stream.  Prints ONE JSON line:
+
+  value / ms_per_step : bytes of all five kernels per step / wall time per step, K steps
+                        bracketed by device synchronisation (inputs already in HBM)
+  kernels             : per kernel, from HIP events recorded on the launch stream around
+                        every launch of the timed region: average / min / median time,
+                        GB/s of algorithmic bytes and the fraction of the 8 TB/s HBM peak
+  roofline            : the same for the kernel that takes the largest share of the step
+  cpu_baseline        : the CPU oracle timed on this machine's host cores on the same
+                        workload (also used to check the GPU results of this run)
+
+Algorithmic bytes: every input element read once and every output element written once
+(16, 16, 24, 24, 16 bytes per element in fp64; half that in fp32).
+"""
+import argparse
+import hashlib
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
+KERNELS = ("copy", "scale", "add", "triad", "dot")
+
+
+def kernel_source_digest():
+    h = hashlib.sha256()
+    for rel in ("paper_2510_00932_amd/csrc/stream_kernels.hpp", "paper_2510_00932_amd/csrc/opal.hip"):
+        with open(os.path.join(ROOT, rel), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload_name, kernel):
+    """HBM bytes per launch from the stored rocprofv3 counter runs, or None when there are
+    none for this workload/kernel or the kernel sources have changed since they were taken."""
+    path = os.path.join(ROOT, "paper_2510_00932_amd", "measured_traffic.json")
+    if not os.path.exists(path):
+        return None
+    with open(path) as f:
+        rec = json.load(f)
+    if rec.get("source_digest") != kernel_source_digest():
+        return None
+    return rec.get("workloads", {}).get(workload_name, {}).get(kernel)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="n2p28_f64", help="name or index of a workload in opal_inputs.WORKLOADS")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing and the result check")
+    ap.add_argument("--cpu-steps", type=int, default=2, help="oracle passes to time (the minimum is reported)")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain torch copy of 1 GiB (a kernel of known traffic, for scaling "
+                         "FETCH_SIZE / WRITE_SIZE counter readings)")
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this path is single-GPU by construction (no sharding, no collectives); "
+              "run it with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import opal_inputs as oi
+    import paper_2510_00932_amd as opal
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the kernels have no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    opal.load()
+
+    wl = oi.workload(int(args.workload) if args.workload.isdigit() else args.workload)
+    n, item = wl.n, wl.itemsize
+    dt = opal.OPAL_F64 if wl.dtype == "f64" else opal.OPAL_F32
+    tdt = torch.float64 if wl.dtype == "f64" else torch.float32
+    dev = torch.device("cuda:0")
+
+    # Inputs: generated on the host, copied once into HBM before anything is timed.
+    host = oi.make_arrays(wl, threads=min(16, os.cpu_count() or 1))
+    off = wl.offset_elems
+    bufs = [torch.empty(n + off + 64, dtype=tdt, device=dev) for _ in range(3)]
+    a, b, c = (buf[off:off + n] for buf in bufs)
+    for d, h in zip((a, b, c), host):
+        d.copy_(torch.from_numpy(h))
+    ws_bytes = opal.opal_dot_workspace_bytes(n, dt)
+    ws = torch.empty(ws_bytes // 8, dtype=torch.float64, device=dev)
+    res = torch.empty(1, dtype=torch.float64, device=dev)
+    stream = torch.cuda.Stream()
+    torch.cuda.synchronize()
+
+    pa, pb, pc = a.data_ptr(), b.data_ptr(), c.data_ptr()
+    pws, pres = ws.data_ptr(), res.data_ptr()
+    s = wl.s
+
+    launches = (
+        lambda: opal.opal_copy(pa, pc, n, dt, stream),
+        lambda: opal.opal_scale(pb, pc, s, n, dt, stream),
+        lambda: opal.opal_add(pa, pb, pc, n, dt, stream),
+        lambda: opal.opal_triad(pa, pb, pc, s, n, dt, stream),
+        lambda: opal.opal_dot(pa, pb, n, dt, pws, ws_bytes, pres, stream),
+    )
+
+    def step(events=None):
+        for k, launch in enumerate(launches):
+            if events is not None:
+                events[k][0].record(stream)
+            launch()
+            if events is not None:
+                events[k][1].record(stream)
+
+    # First step on the pristine inputs: its results are what the oracle check compares.
+    step()
+    stream.synchronize()
+    first = {"a": a.cpu().numpy(), "b": b.cpu().numpy(), "c": c.cpu().numpy(), "dot": float(res.item())} \
+        if not args.no_cpu_baseline else None
+
+    for _ in range(max(0, args.warmup - 1)):
+        step()
+    stream.synchronize()
+    torch.cuda.synchronize()
+
+    K = args.steps
+    events = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in KERNELS]
+              for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        step(events[i])
+    stream.synchronize()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / K
+
+    if args.calibration_copy:
+        src = torch.empty(1 << 27, dtype=torch.float64, device=dev).fill_(1.0)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    bpe = [opal.opal_bytes_per_element(k, dt) for k in range(5)]
+    step_bytes = sum(bpe) * n
+    kernels = {}
+    for k, name in enumerate(KERNELS):
+        ms = [events[i][k][0].elapsed_time(events[i][k][1]) for i in range(K)]
+        nbytes = bpe[k] * n
+        avg, mn, med = sum(ms) / K, min(ms), statistics.median(ms)
+        kernels[name] = {
+            "bytes": nbytes, "avg_us": round(avg * 1e3, 2), "min_us": round(mn * 1e3, 2),
+            "median_us": round(med * 1e3, 2),
+            "GBps_avg": round(nbytes / avg / 1e6, 1), "GBps_best": round(nbytes / mn / 1e6, 1),
+            "GBps_median": round(nbytes / med / 1e6, 1),
+            "frac_of_peak_avg": round(nbytes / avg / 1e6 / HBM_PEAK_GBS, 4),
+        }
+    dominant = max(KERNELS, key=lambda name: kernels[name]["avg_us"])
+    dk = kernels[dominant]
+    roofline = {
+        "kernel": dominant, "bound": "hbm", "achieved": dk["GBps_avg"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": round(dk["GBps_avg"] / HBM_PEAK_GBS, 4),
+        "traffic": measured_traffic(wl.name, dominant),
+        "algorithmic_bytes_per_launch": dk["bytes"], "avg_launch_us": dk["avg_us"],
+    }
+
+    out = {
+        "metric": "achieved HBM GB/s per kernel (copy/scale/add/triad/dot) and % of peak, 1 GPU",
+        "value": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "n": n, "elem_bytes": item, "scalar": s,
+                   "offset_elems": off, "seed": wl.seed, "value_range": [wl.lo, wl.hi],
+                   "step": "copy,scale,add,triad,dot once each", "bytes_per_step": step_bytes},
+        "frac_of_hbm_peak": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "kernels": kernels,
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        ha, hb, hc = host
+        times = []
+        state = None
+        for rep in range(max(1, args.cpu_steps)):
+            xa, xb, xc = ha.copy(), hb.copy(), hc.copy()
+            t0 = time.perf_counter()
+            oracle.copy(xa, xc)
+            oracle.scale(xb, xc, s)
+            oracle.add(xa, xb, xc)
+            oracle.triad(xa, xb, xc, s)
+            r = oracle.dot(xa, xb)
+            times.append(time.perf_counter() - t0)
+            state = (xa, xb, xc, r)
+        best = min(times)
+        out["cpu_baseline"] = {
+            "value": round(step_bytes / best / 1e9, 2), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": "the full workload (n=%d), one step = the same five kernels, best of %d passes, "
+                      "single thread; host has %d logical cores" % (n, len(times), os.cpu_count() or 0),
+            "ms_per_step": round(best * 1e3, 1),
+        }
+        xa, xb, xc, r = state
+        bits = np.uint64 if wl.dtype == "f64" else np.uint32
+        exact = all(np.array_equal(first[k].view(bits), x.view(bits)) for k, x in (("a", xa), ("b", xb), ("c", xc)))
+        rel = abs(first["dot"] - r) / abs(r) if r != 0 else abs(first["dot"])
+        out["check_vs_oracle"] = {"elementwise_bit_exact": bool(exact), "dot_rel_err": float("%.3e" % rel),
+                                  "dot_tolerance": 1e-12 if wl.dtype == "f64" else 1e-5}
+
+    print(json.dumps(out))
+    if "check_vs_oracle" in out:
+        ok = out["check_vs_oracle"]["elementwise_bit_exact"] and \
+            out["check_vs_oracle"]["dot_rel_err"] <= out["check_vs_oracle"]["dot_tolerance"]
+        if not ok:
+            print("bench.py: GPU results differ from the oracle", file=sys.stderr)
+            sys.exit(1)
+
+
+if __name__ == "__main__":
+    main()

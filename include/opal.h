@@ -1,0 +1,102 @@
+/* libopal: the five bandwidth-bound streaming vector kernels that the paper uses
+ * as its "simple", memory-bound optimisation subjects (Table 1: Copy, Mul, Add,
+ * Triad, Dot; Section 5.2), as hand-written HIP kernels for one MI355X
+ * (CDNA4, gfx950) behind a C ABI.
+ *
+ * Common rules for every call
+ *   Pointers   Every array pointer is DEVICE memory owned by the caller; the
+ *              library never allocates, frees, copies to the host or keeps a
+ *              pointer after the call returns.  Arrays are dense, contiguous
+ *              and hold n elements of the type named by `dtype`.
+ *   Alignment  An array pointer only has to be a multiple of its element size
+ *              (8 for OPAL_F64, 4 for OPAL_F32); anything else is
+ *              OPAL_ERR_ALIGN.  Arrays that are 128-byte aligned, or that all
+ *              share one misalignment, run on the fastest path.
+ *   Aliasing   An output array must not overlap an input array of the same
+ *              call (not checked; the result would be undefined).
+ *   Stream     `stream` is a hipStream_t passed as void* (NULL = the default
+ *              stream).  Every call only enqueues work on that stream and
+ *              returns; it never synchronises.
+ *   Scalar     `s` crosses the interface as double.  For OPAL_F32 it is rounded
+ *              once, on the host, to float, and the kernel multiplies by that.
+ *   Rounding   Elementwise results are the IEEE-754 round-to-nearest-even
+ *              result of each single operation in the array's own type; Triad
+ *              rounds the product and then the sum (it is never fused).  They
+ *              are bit-identical to a plain CPU loop compiled without
+ *              floating-point contraction.
+ *   Errors     Only the return value reports errors; nothing is printed or
+ *              thrown.  Argument errors are found on the host before any GPU
+ *              work is enqueued, and then nothing is enqueued.  n == 0 is
+ *              valid: nothing is launched (opal_dot still stores 0.0).
+ *   Sizes      n is a size_t element count; arrays larger than 2 GiB are fine.
+ */
+#ifndef OPAL_H
+#define OPAL_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Status codes (returned as int). */
+enum {
+  OPAL_OK = 0,
+  OPAL_ERR_NULL = 1,      /* a required pointer is NULL while n > 0 (or result/workspace is NULL) */
+  OPAL_ERR_DTYPE = 2,     /* dtype is neither OPAL_F64 nor OPAL_F32 */
+  OPAL_ERR_ALIGN = 3,     /* a pointer is not a multiple of its element size (workspace/result: 8) */
+  OPAL_ERR_WORKSPACE = 4, /* workspace_bytes < opal_dot_workspace_bytes(n, dtype) */
+  OPAL_ERR_LAUNCH = 5     /* the HIP runtime refused a query or a kernel launch */
+};
+
+/* Element types (passed as int). */
+enum { OPAL_F64 = 0, OPAL_F32 = 1 };
+
+/* Copy (Table 1):  c[i] = a[i],  0 <= i < n.
+ * a: device, read, n elements.  c: device, written, n elements. */
+int opal_copy(const void* a, void* c, size_t n, int dtype, void* stream);
+
+/* Mul (Table 1; "scale" here):  b[i] = s * c[i].
+ * c: device, read.  b: device, written.  One rounded multiply per element. */
+int opal_scale(void* b, const void* c, double s, size_t n, int dtype, void* stream);
+
+/* Add (Table 1):  c[i] = a[i] + b[i].
+ * a, b: device, read.  c: device, written.  One rounded add per element. */
+int opal_add(const void* a, const void* b, void* c, size_t n, int dtype, void* stream);
+
+/* Triad (Table 1):  a[i] = b[i] + s * c[i], the product rounded first, then the sum.
+ * b, c: device, read.  a: device, written. */
+int opal_triad(void* a, const void* b, const void* c, double s, size_t n, int dtype, void* stream);
+
+/* Bytes of device workspace opal_dot needs for n elements of `dtype`: room for one
+ * fp64 partial sum per workgroup of its first pass.  A pure host function of its
+ * arguments (no GPU call), at most 64 KiB, and 0 for an unknown dtype. */
+size_t opal_dot_workspace_bytes(size_t n, int dtype);
+
+/* Dot (Table 1):  *result = sum_{i<n} a[i] * b[i].
+ * a, b: device, read.  workspace: device, 8-byte aligned, at least
+ * opal_dot_workspace_bytes(n, dtype) bytes, overwritten.  result: device, one
+ * fp64 (also for OPAL_F32), 8-byte aligned, written.
+ * Two kernels on `stream`: each workgroup of the first writes one fp64 partial
+ * sum to the workspace, the second adds the partials in a fixed order.  No
+ * atomics: for given (pointers' alignment, n, dtype, device) the result is
+ * bit-reproducible from run to run.  OPAL_F64 accumulates in fp64 throughout
+ * (with fused multiply-adds); OPAL_F32 accumulates in fp32 within a thread and
+ * a wavefront and in fp64 from there on.
+ * Calls that share a workspace must be ordered (same stream, or synchronised). */
+int opal_dot(const void* a, const void* b, size_t n, int dtype,
+             void* workspace, size_t workspace_bytes, double* result, void* stream);
+
+/* Static, NUL-terminated description of a status code (never NULL). */
+const char* opal_status_string(int status);
+
+/* Algorithmic bytes per element: every input read once and every output written
+ * once (16/16/24/24/16 for fp64, half that for fp32).  kernel: 0 copy, 1 scale,
+ * 2 add, 3 triad, 4 dot.  Returns 0 for an unknown kernel or dtype. */
+size_t opal_bytes_per_element(int kernel, int dtype);
+
+#ifdef __cplusplus
+}
+#endif
+
+#endif /* OPAL_H */

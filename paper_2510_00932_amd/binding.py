@@ -1,0 +1,137 @@
+"""ctypes binding for libopal.so: argument marshalling only.
+
+Every function mirrors one C entry point of include/opal.h (same name, same
+argument order).  Array arguments are either integers (device addresses) or
+torch tensors on a GPU; a tensor contributes its data_ptr() and, when `dtype`
+is None, its element type.  A non-zero status raises OpalError.
+"""
+import ctypes
+import os
+
+from . import build as _build
+
+OPAL_F64 = 0
+OPAL_F32 = 1
+
+_STATUS_NAMES = {0: "OPAL_OK", 1: "OPAL_ERR_NULL", 2: "OPAL_ERR_DTYPE", 3: "OPAL_ERR_ALIGN",
+                 4: "OPAL_ERR_WORKSPACE", 5: "OPAL_ERR_LAUNCH"}
+
+_LIB = None
+
+
+class OpalError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__("%s (%d): %s" % (_STATUS_NAMES.get(status, "?"), status, message))
+        self.status = status
+
+
+def lib_path() -> str:
+    return _build.LIB
+
+
+def load():
+    """Load libopal.so (building it first only if no built library exists). Never falls back."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = _build.LIB
+    if not os.path.exists(path):
+        _build.build(force=True)
+    elif _build.is_stale():
+        import warnings
+        warnings.warn("libopal.so is older than its sources; rebuild with paper_2510_00932_amd/build.py")
+    lib = ctypes.CDLL(path)
+    vp, sz, it, dbl = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_double
+    lib.opal_copy.argtypes = [vp, vp, sz, it, vp]
+    lib.opal_scale.argtypes = [vp, vp, dbl, sz, it, vp]
+    lib.opal_add.argtypes = [vp, vp, vp, sz, it, vp]
+    lib.opal_triad.argtypes = [vp, vp, vp, dbl, sz, it, vp]
+    lib.opal_dot.argtypes = [vp, vp, sz, it, vp, sz, vp, vp]
+    for name in ("opal_copy", "opal_scale", "opal_add", "opal_triad", "opal_dot"):
+        getattr(lib, name).restype = it
+    lib.opal_dot_workspace_bytes.argtypes = [sz, it]
+    lib.opal_dot_workspace_bytes.restype = sz
+    lib.opal_status_string.argtypes = [it]
+    lib.opal_status_string.restype = ctypes.c_char_p
+    lib.opal_bytes_per_element.argtypes = [it, it]
+    lib.opal_bytes_per_element.restype = sz
+    _LIB = lib
+    return lib
+
+
+def _ptr(x):
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    if hasattr(x, "data_ptr"):
+        if not x.is_cuda:
+            raise TypeError("libopal takes device memory; got a tensor on %s" % x.device)
+        if not x.is_contiguous():
+            raise ValueError("libopal takes dense, contiguous arrays")
+        return x.data_ptr()
+    raise TypeError("expected a device address (int) or a torch GPU tensor, got %r" % type(x))
+
+
+def _stream(stream):
+    if stream is None:
+        return None
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream        # torch.cuda.Stream
+
+
+def _dtype_of(x, dtype):
+    if dtype is not None:
+        return dtype
+    if hasattr(x, "dtype"):
+        name = str(x.dtype)
+        if name.endswith("float64"):
+            return OPAL_F64
+        if name.endswith("float32"):
+            return OPAL_F32
+        raise TypeError("libopal supports float64 and float32 arrays, got %s" % name)
+    raise TypeError("dtype must be given when arrays are passed as addresses")
+
+
+def _check(status):
+    if status != 0:
+        raise OpalError(status, opal_status_string(status))
+
+
+def opal_status_string(status: int) -> str:
+    return load().opal_status_string(int(status)).decode()
+
+
+def opal_bytes_per_element(kernel: int, dtype: int) -> int:
+    return int(load().opal_bytes_per_element(int(kernel), int(dtype)))
+
+
+def opal_copy(a, c, n, dtype=None, stream=None):
+    """c[i] = a[i]."""
+    _check(load().opal_copy(_ptr(a), _ptr(c), n, _dtype_of(a, dtype), _stream(stream)))
+
+
+def opal_scale(b, c, s, n, dtype=None, stream=None):
+    """b[i] = s * c[i]."""
+    _check(load().opal_scale(_ptr(b), _ptr(c), float(s), n, _dtype_of(c, dtype), _stream(stream)))
+
+
+def opal_add(a, b, c, n, dtype=None, stream=None):
+    """c[i] = a[i] + b[i]."""
+    _check(load().opal_add(_ptr(a), _ptr(b), _ptr(c), n, _dtype_of(a, dtype), _stream(stream)))
+
+
+def opal_triad(a, b, c, s, n, dtype=None, stream=None):
+    """a[i] = b[i] + s * c[i]."""
+    _check(load().opal_triad(_ptr(a), _ptr(b), _ptr(c), float(s), n, _dtype_of(b, dtype), _stream(stream)))
+
+
+def opal_dot_workspace_bytes(n, dtype) -> int:
+    return int(load().opal_dot_workspace_bytes(n, int(dtype)))
+
+
+def opal_dot(a, b, n, dtype, workspace, workspace_bytes, result, stream=None):
+    """result[0] = sum a[i]*b[i] (result: one fp64 in device memory)."""
+    _check(load().opal_dot(_ptr(a), _ptr(b), n, _dtype_of(a, dtype), _ptr(workspace), workspace_bytes,
+                           _ptr(result), _stream(stream)))

@@ -1,0 +1,218 @@
+// Host side of libopal: argument checks, work split and kernel launches for the
+// five streaming vector kernels (Table 1: Copy, Mul, Add, Triad, Dot).  The
+// interface contract is written out in include/opal.h.
+//
+// Built for gfx950 only:
+//   hipcc --offload-arch=gfx950 -O3 -ffp-contract=off \
+//         -Xclang -target-feature -Xclang -packed-fp32-ops -shared -fPIC
+
+#include "../../include/opal.h"
+#include "stream_kernels.hpp"
+
+namespace {
+
+using namespace opal;
+
+// Launch shape.  A workgroup of kBlock threads moves tiles of kBlock * U
+// 16-byte vectors; the grid is capped at kGroupsPerCU workgroups per compute
+// unit (all resident at once: 8 x 256 threads fill a CU's 2048 thread slots),
+// each looping over its share of the tiles.
+constexpr unsigned kBlock = 256;
+constexpr int kUnrollOne = 4;     // Copy, Scale: one input stream
+constexpr int kUnrollTwo = 4;     // Add, Triad: two input streams
+constexpr int kUnrollDot = 4;
+constexpr unsigned kGroupsPerCU = 8;
+constexpr bool kNtLoad = true;
+constexpr bool kNtStore = true;
+constexpr unsigned kDotMaxGroups = 8192;   // 64 KiB of fp64 partials at most
+constexpr unsigned kFinalBlock = 256;
+constexpr unsigned kBodyAlign = 128;       // the vector body starts on a 128-byte line
+
+constexpr int kMaxDevices = 64;
+
+// Compute units of the current device (cached per device id); 0 on failure.
+unsigned compute_units() {
+  static int cached[kMaxDevices];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 0;
+  if (dev >= 0 && dev < kMaxDevices && cached[dev] > 0) return (unsigned)cached[dev];
+  int cus = 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+    return 0;
+  if (dev >= 0 && dev < kMaxDevices) cached[dev] = cus;
+  return (unsigned)cus;
+}
+
+struct Split {
+  unsigned head;   // scalar elements before the body
+  size_t nvec;     // 16-byte vectors in the body
+};
+
+// Head = elements from `steer` up to its next kBodyAlign-byte boundary (or all n).
+template <typename T>
+Split split(const void* steer, size_t n) {
+  constexpr size_t L = 16 / sizeof(T);
+  const uintptr_t addr = reinterpret_cast<uintptr_t>(steer);
+  size_t head = ((kBodyAlign - (addr % kBodyAlign)) % kBodyAlign) / sizeof(T);
+  if (head > n) head = n;
+  return Split{(unsigned)head, (n - head) / L};
+}
+
+bool aligned16_after(const void* p, unsigned head, size_t elem) {
+  return ((reinterpret_cast<uintptr_t>(p) + (uintptr_t)head * elem) & 15u) == 0;
+}
+
+size_t full_tiles_of(size_t nvec, int unroll) { return nvec / ((size_t)kBlock * (size_t)unroll); }
+
+unsigned grid_for(size_t nvec, int unroll, unsigned cap) {
+  const size_t tiles = full_tiles_of(nvec, unroll);
+  size_t g = tiles < 1 ? 1 : tiles;
+  if (g > cap) g = cap;
+  return (unsigned)g;
+}
+
+int check_ptr(const void* p, size_t n, size_t elem) {
+  if (n == 0) return OPAL_OK;
+  if (p == nullptr) return OPAL_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(p) % elem != 0) return OPAL_ERR_ALIGN;
+  return OPAL_OK;
+}
+
+template <typename T, Op OP>
+int launch_stream(T* out, const T* in0, const T* in1, T s, size_t n, hipStream_t stream) {
+  constexpr int U = kTwoInputs<OP> ? kUnrollTwo : kUnrollOne;
+  const unsigned cus = compute_units();
+  if (cus == 0) return OPAL_ERR_LAUNCH;
+  const Split sp = split<T>(out, n);
+  const bool aligned = aligned16_after(in0, sp.head, sizeof(T)) &&
+                       (!kTwoInputs<OP> || aligned16_after(in1, sp.head, sizeof(T)));
+  const unsigned grid = grid_for(sp.nvec, U, cus * kGroupsPerCU);
+  if (aligned) {
+    hipLaunchKernelGGL((stream_kernel<T, OP, U, true, kNtLoad, kNtStore>), dim3(grid), dim3(kBlock), 0,
+                       stream, out, in0, in1, s, sp.head, sp.nvec, full_tiles_of(sp.nvec, U), n);
+  } else {
+    hipLaunchKernelGGL((stream_kernel<T, OP, U, false, kNtLoad, kNtStore>), dim3(grid), dim3(kBlock), 0,
+                       stream, out, in0, in1, s, sp.head, sp.nvec, full_tiles_of(sp.nvec, U), n);
+  }
+  return hipGetLastError() == hipSuccess ? OPAL_OK : OPAL_ERR_LAUNCH;
+}
+
+template <Op OP>
+int elementwise(void* out, const void* in0, const void* in1, double s, size_t n, int dtype, void* stream) {
+  if (dtype != OPAL_F64 && dtype != OPAL_F32) return OPAL_ERR_DTYPE;
+  const size_t elem = dtype == OPAL_F64 ? 8 : 4;
+  int st = check_ptr(out, n, elem);
+  if (st == OPAL_OK) st = check_ptr(in0, n, elem);
+  if (st == OPAL_OK && kTwoInputs<OP>) st = check_ptr(in1, n, elem);
+  if (st != OPAL_OK) return st;
+  if (n == 0) return OPAL_OK;
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  if (dtype == OPAL_F64) {
+    return launch_stream<double, OP>(static_cast<double*>(out), static_cast<const double*>(in0),
+                                     static_cast<const double*>(in1), s, n, hs);
+  }
+  return launch_stream<float, OP>(static_cast<float*>(out), static_cast<const float*>(in0),
+                                  static_cast<const float*>(in1), (float)s, n, hs);
+}
+
+// Upper bound, from n alone, on the workgroups of dot's first pass.
+unsigned dot_groups_bound(size_t n, int dtype) {
+  const size_t lanes = dtype == OPAL_F64 ? 2 : 4;
+  const size_t tiles = n / ((size_t)kBlock * kUnrollDot * lanes);
+  size_t g = tiles < 1 ? 1 : tiles;
+  if (g > kDotMaxGroups) g = kDotMaxGroups;
+  return (unsigned)g;
+}
+
+template <typename T>
+int launch_dot(const T* a, const T* b, size_t n, double* partials, double* result, hipStream_t stream) {
+  unsigned groups = 0;
+  if (n > 0) {
+    const unsigned cus = compute_units();
+    if (cus == 0) return OPAL_ERR_LAUNCH;
+    const Split sp = split<T>(a, n);
+    const bool aligned = aligned16_after(b, sp.head, sizeof(T));
+    unsigned cap = cus * kGroupsPerCU;
+    const unsigned bound = dot_groups_bound(n, sizeof(T) == 8 ? OPAL_F64 : OPAL_F32);
+    if (cap > bound) cap = bound;
+    groups = grid_for(sp.nvec, kUnrollDot, cap);
+    if (aligned) {
+      hipLaunchKernelGGL((dot_partial_kernel<T, kUnrollDot, true, kNtLoad>), dim3(groups), dim3(kBlock), 0,
+                         stream, a, b, partials, sp.head, sp.nvec, full_tiles_of(sp.nvec, kUnrollDot), n);
+    } else {
+      hipLaunchKernelGGL((dot_partial_kernel<T, kUnrollDot, false, kNtLoad>), dim3(groups), dim3(kBlock), 0,
+                         stream, a, b, partials, sp.head, sp.nvec, full_tiles_of(sp.nvec, kUnrollDot), n);
+    }
+    if (hipGetLastError() != hipSuccess) return OPAL_ERR_LAUNCH;
+  }
+  hipLaunchKernelGGL(dot_final_kernel, dim3(1), dim3(kFinalBlock), 0, stream, partials, groups, result);
+  return hipGetLastError() == hipSuccess ? OPAL_OK : OPAL_ERR_LAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+int opal_copy(const void* a, void* c, size_t n, int dtype, void* stream) {
+  return elementwise<Op::Copy>(c, a, nullptr, 0.0, n, dtype, stream);
+}
+
+int opal_scale(void* b, const void* c, double s, size_t n, int dtype, void* stream) {
+  return elementwise<Op::Scale>(b, c, nullptr, s, n, dtype, stream);
+}
+
+int opal_add(const void* a, const void* b, void* c, size_t n, int dtype, void* stream) {
+  return elementwise<Op::Add>(c, a, b, 0.0, n, dtype, stream);
+}
+
+int opal_triad(void* a, const void* b, const void* c, double s, size_t n, int dtype, void* stream) {
+  return elementwise<Op::Triad>(a, b, c, s, n, dtype, stream);
+}
+
+size_t opal_dot_workspace_bytes(size_t n, int dtype) {
+  if (dtype != OPAL_F64 && dtype != OPAL_F32) return 0;
+  return (size_t)dot_groups_bound(n, dtype) * sizeof(double);
+}
+
+int opal_dot(const void* a, const void* b, size_t n, int dtype, void* workspace, size_t workspace_bytes,
+             double* result, void* stream) {
+  if (dtype != OPAL_F64 && dtype != OPAL_F32) return OPAL_ERR_DTYPE;
+  const size_t elem = dtype == OPAL_F64 ? 8 : 4;
+  int st = check_ptr(a, n, elem);
+  if (st == OPAL_OK) st = check_ptr(b, n, elem);
+  if (st != OPAL_OK) return st;
+  if (result == nullptr || workspace == nullptr) return OPAL_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(result) % 8 != 0 || reinterpret_cast<uintptr_t>(workspace) % 8 != 0)
+    return OPAL_ERR_ALIGN;
+  if (workspace_bytes < opal_dot_workspace_bytes(n, dtype)) return OPAL_ERR_WORKSPACE;
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  double* partials = static_cast<double*>(workspace);
+  if (dtype == OPAL_F64) {
+    return launch_dot<double>(static_cast<const double*>(a), static_cast<const double*>(b), n, partials, result, hs);
+  }
+  return launch_dot<float>(static_cast<const float*>(a), static_cast<const float*>(b), n, partials, result, hs);
+}
+
+const char* opal_status_string(int status) {
+  switch (status) {
+    case OPAL_OK: return "ok";
+    case OPAL_ERR_NULL: return "a required pointer is NULL";
+    case OPAL_ERR_DTYPE: return "dtype is neither OPAL_F64 nor OPAL_F32";
+    case OPAL_ERR_ALIGN: return "a pointer is not aligned to its element size";
+    case OPAL_ERR_WORKSPACE: return "dot workspace is smaller than opal_dot_workspace_bytes(n, dtype)";
+    case OPAL_ERR_LAUNCH: return "the HIP runtime refused a query or a kernel launch";
+    default: return "unknown status";
+  }
+}
+
+size_t opal_bytes_per_element(int kernel, int dtype) {
+  if (dtype != OPAL_F64 && dtype != OPAL_F32) return 0;
+  const size_t w = dtype == OPAL_F64 ? 8 : 4;
+  switch (kernel) {
+    case 0: case 1: case 4: return 2 * w;
+    case 2: case 3: return 3 * w;
+    default: return 0;
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,194 @@
+"""Parity of the HIP kernels with the CPU oracle, through the C ABI, on a real MI355X.
+
+Elementwise kernels: bit-exact.  Dot: relative error <= 1e-12 (fp64) / 1e-5 (fp32)
+against the oracle's compensated long-double sum.
+"""
+import numpy as np
+import pytest
+import torch
+
+import opal_inputs as oi
+import paper_2510_00932_amd as opal
+
+pytestmark = pytest.mark.gpu
+
+DTYPES = [np.float64, np.float32]
+
+# around one vector, one wavefront, one workgroup, one tile, and the point where the
+# grid stops growing and workgroups start looping over several tiles
+SMALL_SIZES = [0, 1, 2, 3, 4, 5, 7, 8, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257,
+               511, 512, 513, 1023, 1024, 1025, 2047, 2048, 2049, 4095, 4096, 4097, 8191, 8192, 8193]
+MID_SIZES = [65535, 65536, 65537, (1 << 20) - 1, (1 << 20) + 1, 1572869]
+LARGE_SIZES = [(1 << 22) - 1, (1 << 22) + 1, (1 << 23) + 2049, (1 << 24) + 12345, 3 * (1 << 23) + 7]
+OFFSETS = [(0, 0, 0), (1, 1, 1), (1, 0, 0), (0, 1, 0), (0, 0, 1), (3, 2, 1), (1, 2, 3), (5, 5, 5)]
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    opal.load()
+    return torch.device("cuda:0")
+
+
+@pytest.fixture(scope="module")
+def parity(gpu):
+    import parity as _parity
+    return _parity
+
+
+@pytest.fixture(scope="module")
+def harness(gpu):
+    import gpu_harness
+    return gpu_harness
+
+
+# ------------------------------------------------------------------ the pins, on the GPU
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_pins_hold_on_the_gpu(harness, dtype):
+    import pins
+    tol = 1e-12 if dtype == np.float64 else 1e-5
+    for offsets in [(0, 0, 0), (1, 1, 1), (1, 2, 3)]:
+        impl = harness.GpuImpl(offsets)
+        for n in (0, 1, 5, 1000, 70001):
+            pins.pin_constant_fill(impl, dtype, n)
+            pins.pin_ramp(impl, dtype, n)
+        pins.pin_exact_rational_elementwise(impl, dtype, n=700)
+        pins.pin_fma_discriminator(impl, dtype, n=1)
+        pins.pin_fma_discriminator(impl, dtype, n=5000)
+        pins.pin_exact_dyadic_chain(impl, dtype, n=3000, dot_rel_tol=tol)
+        pins.pin_dot_closed_forms(impl, dtype, [0, 1, 2, 3, 65, 1000, 4097, 100003])
+        pins.pin_dot_exact_rational(impl, dtype, 3000, rel_tol=tol)
+        pins.pin_dot_exact_rational(impl, dtype, 3000, rel_tol=tol, lo=0.5, hi=1.5)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_closed_forms_at_large_sizes(harness, dtype):
+    """Facts that hold at any n, at sizes where every workgroup loops over several tiles."""
+    import pins
+    impl = harness.GpuImpl((0, 0, 0))
+    n = (1 << 25) + 4099
+    pins.pin_constant_fill(impl, dtype, n)
+    pins.pin_ramp(impl, dtype, n)
+    pins.pin_fma_discriminator(impl, dtype, n=n)
+    pins.pin_dot_closed_forms(impl, dtype, [n])
+    impl = harness.GpuImpl((1, 1, 1))
+    pins.pin_ramp(impl, dtype, n)
+    pins.pin_dot_closed_forms(impl, dtype, [n])
+
+
+# ------------------------------------------------------------------ vs the oracle
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_size_and_alignment_sweep(parity, dtype):
+    w = oi.workload(4)  # sign-mixed values, s = -0.75
+    full = [oi.uniform_array(w.seed, k, max(SMALL_SIZES + MID_SIZES), dtype, w.lo, w.hi) for k in range(3)]
+    for n in SMALL_SIZES + MID_SIZES:
+        for offsets in OFFSETS if n <= 8193 else OFFSETS[:4]:
+            parity.run_chain([x[:n].copy() for x in full], w.s, offsets)
+    w = oi.workload(0)  # positive values, s = 0.4
+    full = [oi.uniform_array(w.seed, k, 8193, dtype, w.lo, w.hi) for k in range(3)]
+    for n in SMALL_SIZES:
+        parity.run_chain([x[:n].copy() for x in full], w.s, (0, 0, 0))
+        parity.run_fresh([x[:n].copy() for x in full], w.s, (1, 0, 3))
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_large_ragged_sizes(parity, dtype):
+    w = oi.workload(4)
+    full = [oi.uniform_array(w.seed, k, max(LARGE_SIZES), dtype, w.lo, w.hi) for k in range(3)]
+    for n, offsets in zip(LARGE_SIZES, [(0, 0, 0), (1, 1, 1), (1, 0, 2), (0, 0, 0), (3, 3, 3)]):
+        parity.run_chain([x[:n].copy() for x in full], w.s, offsets)
+        parity.run_fresh([x[:n].copy() for x in full], w.s, offsets)
+
+
+def test_workload_0_chained_and_fresh(parity):
+    w = oi.workload(0)
+    arrays = oi.make_arrays(w)
+    rel, kappa = parity.run_chain(arrays, w.s)
+    assert kappa < 1.0 + 1e-9          # every term of the chained dot has one sign
+    parity.run_fresh(arrays, w.s)
+
+
+def test_idempotent_under_repeated_launches(parity):
+    w = oi.workload(0)
+    parity.run_chain(oi.make_arrays(w, n=(1 << 18) + 77), w.s, (1, 1, 1), iters=20)
+
+
+def test_on_a_side_stream(parity):
+    s = torch.cuda.Stream()
+    w = oi.workload(0)
+    arrays = oi.make_arrays(w, n=(1 << 18) + 3)
+    parity.run_chain(arrays, w.s, (0, 0, 0), stream=s)
+    parity.run_fresh(arrays, w.s, (1, 1, 1), stream=s)
+
+
+@pytest.mark.parametrize("index", [1, 2, 3, 4])
+def test_full_size_workloads(parity, index):
+    """The four large workloads at their full sizes, every output element compared."""
+    w = oi.workload(index)
+    arrays = oi.make_arrays(w, threads=16)
+    off = (w.offset_elems,) * 3
+    rel_c, kappa_c = parity.run_chain(arrays, w.s, off, check_all_arrays_each_step=False)
+    rel_f, kappa_f = parity.run_fresh(arrays, w.s, off)
+    print("\n%s: chained dot rel err %.2e (kappa %.2e); fresh dot rel err %.2e (kappa %.2e)"
+          % (w.name, rel_c, kappa_c, rel_f, kappa_f))
+    if index == 4:
+        assert kappa_f > 100.0          # the fresh dot of this workload really is sign-mixed
+
+
+# ------------------------------------------------------------------ boundary behaviour on the device
+
+def test_zero_length_dot_stores_zero(harness):
+    res = torch.full((1,), float("nan"), dtype=torch.float64, device="cuda:0")
+    ws = torch.zeros(16, dtype=torch.float64, device="cuda:0")
+    for dt in (opal.OPAL_F64, opal.OPAL_F32):
+        res.fill_(float("nan"))
+        opal.opal_dot(0, 0, 0, dt, ws.data_ptr(), 128, res.data_ptr(), None)
+        torch.cuda.synchronize()
+        assert res.item() == 0.0
+
+
+def test_errors_enqueue_nothing(harness):
+    n = 4096
+    a = harness.GuardedArray(n, np.float64).upload(np.ones(n))
+    c = harness.GuardedArray(n, np.float64).upload(np.zeros(n))
+    with pytest.raises(opal.OpalError) as e:
+        opal.opal_copy(a.ptr + 4, c.ptr, n, opal.OPAL_F64, None)
+    assert e.value.status == 3
+    with pytest.raises(opal.OpalError) as e:
+        opal.opal_copy(a.ptr, c.ptr, n, 3, None)
+    assert e.value.status == 2
+    res = torch.full((1,), 7.0, dtype=torch.float64, device="cuda:0")
+    ws = torch.zeros(8, dtype=torch.float64, device="cuda:0")
+    with pytest.raises(opal.OpalError) as e:
+        opal.opal_dot(a.ptr, c.ptr, 1 << 20, opal.OPAL_F64, ws.data_ptr(), 0, res.data_ptr(), None)
+    assert e.value.status == 4
+    torch.cuda.synchronize()
+    assert (c.download() == 0).all() and res.item() == 7.0
+
+
+def test_tensor_arguments(harness):
+    n = 10007
+    w = oi.workload(0)
+    ha, hb, hc = oi.make_arrays(w, n=n)
+    a, b, c = (torch.from_numpy(x).cuda() for x in (ha, hb, hc))
+    opal.opal_triad(a, b, c, w.s, n)
+    torch.cuda.synchronize()
+    import oracle
+    oracle.triad(ha, hb, hc, w.s)
+    assert np.array_equal(a.cpu().numpy().view(np.uint64), ha.view(np.uint64))
+
+
+def test_against_torch_as_a_sanity_check(harness):
+    n = (1 << 20) + 5
+    w = oi.workload(4)
+    ha, hb, hc = oi.make_arrays(w, n=n)
+    a, b, c = (torch.from_numpy(x).cuda() for x in (ha, hb, hc))
+    out = torch.empty_like(a)
+    opal.opal_add(a, b, out, n)
+    assert torch.equal(out, a + b)
+    opal.opal_scale(out, c, w.s, n)
+    assert torch.equal(out, c * w.s)
+    r = harness.dot_device(a.data_ptr(), b.data_ptr(), n, opal.OPAL_F64)
+    assert abs(r - torch.dot(a, b).item()) <= 1e-9 * n
