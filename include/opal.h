@@ -90,6 +90,10 @@ int opal_dot(const void* a, const void* b, size_t n, int dtype,
 /* Static, NUL-terminated description of a status code (never NULL). */
 const char* opal_status_string(int status);
 
+/* Name of the last HIP runtime error the calling thread met inside this library
+ * ("hipSuccess" if none): the detail behind an OPAL_ERR_LAUNCH.  Static string. */
+const char* opal_last_hip_error(void);
+
 /* Algorithmic bytes per element: every input read once and every output written
  * once (16/16/24/24/16 for fp64, half that for fp32).  kernel: 0 copy, 1 scale,
  * 2 add, 3 triad, 4 dot.  Returns 0 for an unknown kernel or dtype. */

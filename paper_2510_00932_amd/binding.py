@@ -34,6 +34,13 @@ def load():
     global _LIB
     if _LIB is not None:
         return _LIB
+    # torch ships its own copy of the HIP runtime.  Importing it first makes the
+    # dynamic linker bind libopal.so to that same copy, so that streams and device
+    # pointers created by torch are the runtime's own when the library sees them.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     path = _build.LIB
     if not os.path.exists(path):
         _build.build(force=True)
@@ -53,6 +60,8 @@ def load():
     lib.opal_dot_workspace_bytes.restype = sz
     lib.opal_status_string.argtypes = [it]
     lib.opal_status_string.restype = ctypes.c_char_p
+    lib.opal_last_hip_error.argtypes = []
+    lib.opal_last_hip_error.restype = ctypes.c_char_p
     lib.opal_bytes_per_element.argtypes = [it, it]
     lib.opal_bytes_per_element.restype = sz
     _LIB = lib
@@ -96,7 +105,10 @@ def _dtype_of(x, dtype):
 
 def _check(status):
     if status != 0:
-        raise OpalError(status, opal_status_string(status))
+        detail = opal_status_string(status)
+        if status == 5:
+            detail += " [%s]" % load().opal_last_hip_error().decode()
+        raise OpalError(status, detail)
 
 
 def opal_status_string(status: int) -> str:

@@ -30,14 +30,33 @@ constexpr unsigned kBodyAlign = 128;       // the vector body starts on a 128-by
 
 constexpr int kMaxDevices = 64;
 
+// Last HIP error this thread met inside the library (hipSuccess if none yet).
+thread_local hipError_t g_last_hip_error = hipSuccess;
+
+bool hip_ok(hipError_t e) {
+  if (e != hipSuccess) g_last_hip_error = e;
+  return e == hipSuccess;
+}
+
+// Launches through the call that returns its own status, so an error left behind
+// by some earlier, unrelated runtime call of the process is never mistaken for ours.
+template <typename... Params, typename... Args>
+bool launch(void (*kernel)(Params...), unsigned grid, unsigned block, hipStream_t stream, Args... args) {
+  auto pack = [&](Params... p) {
+    void* argv[] = {static_cast<void*>(&p)...};
+    return hipLaunchKernel(reinterpret_cast<const void*>(kernel), dim3(grid), dim3(block), argv, 0, stream);
+  };
+  return hip_ok(pack(args...));
+}
+
 // Compute units of the current device (cached per device id); 0 on failure.
 unsigned compute_units() {
   static int cached[kMaxDevices];
   int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess) return 0;
+  if (!hip_ok(hipGetDevice(&dev))) return 0;
   if (dev >= 0 && dev < kMaxDevices && cached[dev] > 0) return (unsigned)cached[dev];
   int cus = 0;
-  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+  if (!hip_ok(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) || cus <= 0)
     return 0;
   if (dev >= 0 && dev < kMaxDevices) cached[dev] = cus;
   return (unsigned)cus;
@@ -87,14 +106,13 @@ int launch_stream(T* out, const T* in0, const T* in1, T s, size_t n, hipStream_t
   const bool aligned = aligned16_after(in0, sp.head, sizeof(T)) &&
                        (!kTwoInputs<OP> || aligned16_after(in1, sp.head, sizeof(T)));
   const unsigned grid = grid_for(sp.nvec, U, cus * kGroupsPerCU);
-  if (aligned) {
-    hipLaunchKernelGGL((stream_kernel<T, OP, U, true, kNtLoad, kNtStore>), dim3(grid), dim3(kBlock), 0,
-                       stream, out, in0, in1, s, sp.head, sp.nvec, full_tiles_of(sp.nvec, U), n);
-  } else {
-    hipLaunchKernelGGL((stream_kernel<T, OP, U, false, kNtLoad, kNtStore>), dim3(grid), dim3(kBlock), 0,
-                       stream, out, in0, in1, s, sp.head, sp.nvec, full_tiles_of(sp.nvec, U), n);
-  }
-  return hipGetLastError() == hipSuccess ? OPAL_OK : OPAL_ERR_LAUNCH;
+  const size_t tiles = full_tiles_of(sp.nvec, U);
+  const bool ok =
+      aligned ? launch(stream_kernel<T, OP, U, true, kNtLoad, kNtStore>, grid, kBlock, stream, out, in0, in1, s,
+                       sp.head, sp.nvec, tiles, n)
+              : launch(stream_kernel<T, OP, U, false, kNtLoad, kNtStore>, grid, kBlock, stream, out, in0, in1, s,
+                       sp.head, sp.nvec, tiles, n);
+  return ok ? OPAL_OK : OPAL_ERR_LAUNCH;
 }
 
 template <Op OP>
@@ -136,17 +154,15 @@ int launch_dot(const T* a, const T* b, size_t n, double* partials, double* resul
     const unsigned bound = dot_groups_bound(n, sizeof(T) == 8 ? OPAL_F64 : OPAL_F32);
     if (cap > bound) cap = bound;
     groups = grid_for(sp.nvec, kUnrollDot, cap);
-    if (aligned) {
-      hipLaunchKernelGGL((dot_partial_kernel<T, kUnrollDot, true, kNtLoad>), dim3(groups), dim3(kBlock), 0,
-                         stream, a, b, partials, sp.head, sp.nvec, full_tiles_of(sp.nvec, kUnrollDot), n);
-    } else {
-      hipLaunchKernelGGL((dot_partial_kernel<T, kUnrollDot, false, kNtLoad>), dim3(groups), dim3(kBlock), 0,
-                         stream, a, b, partials, sp.head, sp.nvec, full_tiles_of(sp.nvec, kUnrollDot), n);
-    }
-    if (hipGetLastError() != hipSuccess) return OPAL_ERR_LAUNCH;
+    const size_t tiles = full_tiles_of(sp.nvec, kUnrollDot);
+    const bool ok = aligned ? launch(dot_partial_kernel<T, kUnrollDot, true, kNtLoad>, groups, kBlock, stream, a, b,
+                                     partials, sp.head, sp.nvec, tiles, n)
+                            : launch(dot_partial_kernel<T, kUnrollDot, false, kNtLoad>, groups, kBlock, stream, a, b,
+                                     partials, sp.head, sp.nvec, tiles, n);
+    if (!ok) return OPAL_ERR_LAUNCH;
   }
-  hipLaunchKernelGGL(dot_final_kernel, dim3(1), dim3(kFinalBlock), 0, stream, partials, groups, result);
-  return hipGetLastError() == hipSuccess ? OPAL_OK : OPAL_ERR_LAUNCH;
+  const double* cpartials = partials;
+  return launch(dot_final_kernel, 1u, kFinalBlock, stream, cpartials, groups, result) ? OPAL_OK : OPAL_ERR_LAUNCH;
 }
 
 }  // namespace
@@ -204,6 +220,8 @@ const char* opal_status_string(int status) {
     default: return "unknown status";
   }
 }
+
+const char* opal_last_hip_error(void) { return hipGetErrorName(g_last_hip_error); }
 
 size_t opal_bytes_per_element(int kernel, int dtype) {
   if (dtype != OPAL_F64 && dtype != OPAL_F32) return 0;

@@ -28,7 +28,7 @@ class GuardedArray:
         self.raw = torch.full((nbytes,), SENTINEL, dtype=torch.uint8, device=device)
         assert self.raw.data_ptr() % 256 == 0, "torch device allocations are expected to be 256-byte aligned"
         self.view = self.raw[self.off:self.off + n * item].view(_TORCH[self.np_dtype])
-        assert self.view.data_ptr() == self.raw.data_ptr() + self.off
+        assert n == 0 or self.view.data_ptr() == self.raw.data_ptr() + self.off
 
     @property
     def ptr(self):
