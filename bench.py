@@ -63,6 +63,9 @@ def main():
     ap.add_argument("--workload", default="n2p28_f64", help="name or index of a workload in opal_inputs.WORKLOADS")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing and the result check")
     ap.add_argument("--cpu-steps", type=int, default=2, help="oracle passes to time (the minimum is reported)")
+    ap.add_argument("--skew-bytes", type=int, default=0,
+                    help="extra bytes between the starts of consecutive arrays beyond the array size (the arrays "
+                         "are carved out of one allocation at base + k * (array bytes + skew), k = 0, 1, 2)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain torch copy of 1 GiB (a kernel of known traffic, for scaling "
                          "FETCH_SIZE / WRITE_SIZE counter readings)")
@@ -93,8 +96,13 @@ def main():
     # Inputs: generated on the host, copied once into HBM before anything is timed.
     host = oi.make_arrays(wl, threads=min(16, os.cpu_count() or 1))
     off = wl.offset_elems
-    bufs = [torch.empty(n + off + 64, dtype=tdt, device=dev) for _ in range(3)]
-    a, b, c = (buf[off:off + n] for buf in bufs)
+    if args.skew_bytes % 256 != 0 or args.skew_bytes < 0:
+        print("bench.py: --skew-bytes must be a non-negative multiple of 256", file=sys.stderr)
+        sys.exit(2)
+    pitch = ((n + off) * item + 255) // 256 * 256 + args.skew_bytes      # bytes from one array's base to the next
+    pool = torch.empty(3 * pitch + 256, dtype=torch.uint8, device=dev)
+    assert pool.data_ptr() % 256 == 0
+    a, b, c = (pool[k * pitch + off * item:k * pitch + (off + n) * item].view(tdt) for k in range(3))
     for d, h in zip((a, b, c), host):
         d.copy_(torch.from_numpy(h))
     ws_bytes = opal.opal_dot_workspace_bytes(n, dt)
@@ -186,7 +194,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "n": n, "elem_bytes": item, "scalar": s,
-                   "offset_elems": off, "seed": wl.seed, "value_range": [wl.lo, wl.hi],
+                   "offset_elems": off, "array_pitch_bytes": pitch, "seed": wl.seed, "value_range": [wl.lo, wl.hi],
                    "step": "copy,scale,add,triad,dot once each", "bytes_per_step": step_bytes},
         "frac_of_hbm_peak": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "kernels": kernels,

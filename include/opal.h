@@ -46,7 +46,8 @@ enum {
   OPAL_ERR_DTYPE = 2,     /* dtype is neither OPAL_F64 nor OPAL_F32 */
   OPAL_ERR_ALIGN = 3,     /* a pointer is not a multiple of its element size (workspace/result: 8) */
   OPAL_ERR_WORKSPACE = 4, /* workspace_bytes < opal_dot_workspace_bytes(n, dtype) */
-  OPAL_ERR_LAUNCH = 5     /* the HIP runtime refused a query or a kernel launch */
+  OPAL_ERR_LAUNCH = 5,    /* the HIP runtime refused a query or a kernel launch */
+  OPAL_ERR_SIZE = 6       /* n needs more than 2^31 - 1 workgroups (n >= 2^37 vectors' worth) */
 };
 
 /* Element types (passed as int). */

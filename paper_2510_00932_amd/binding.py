@@ -14,7 +14,7 @@ OPAL_F64 = 0
 OPAL_F32 = 1
 
 _STATUS_NAMES = {0: "OPAL_OK", 1: "OPAL_ERR_NULL", 2: "OPAL_ERR_DTYPE", 3: "OPAL_ERR_ALIGN",
-                 4: "OPAL_ERR_WORKSPACE", 5: "OPAL_ERR_LAUNCH"}
+                 4: "OPAL_ERR_WORKSPACE", 5: "OPAL_ERR_LAUNCH", 6: "OPAL_ERR_SIZE"}
 
 _LIB = None
 

@@ -1,24 +1,36 @@
 // Device code for the five streaming vector kernels (Table 1: Copy, Mul, Add,
 // Triad, Dot), written for CDNA4 / gfx950 only: 64-lane wavefronts, 128-bit
-// global loads and stores, no LDS on the elementwise path, DPP lane exchanges
-// for the dot reduction.  Nothing here is a contraction, so no MFMA.
+// non-temporal global loads and stores, no LDS on the elementwise path, DPP
+// lane exchanges for the dot reduction.  Nothing here is a contraction, so no
+// MFMA.
 //
-// Work decomposition (all kernels)
-//   An array of n elements is split, on the host, into
-//     head  : scalar elements up to the first 128-byte boundary of the array
-//             that steers the split (the output; for dot, `a`)
-//     body  : nvec 16-byte vectors (double2 / float4)
-//     tail  : the < one-vector remainder.
-//   The body is cut into tiles of blockDim.x * U vectors.  Workgroup g takes
-//   tiles g, g + G, g + 2G, ... (G = gridDim.x): at any moment the resident
-//   workgroups sweep one contiguous window of each array, which keeps DRAM
-//   pages and TLB entries few.  Inside a tile, lane l of the workgroup touches
-//   vectors l, l + B, ..., l + (U-1)B, so every wavefront-wide access is one
-//   contiguous 1 KiB run, and each thread has U (x inputs) independent 16-byte
-//   loads in flight before its first use.
-//   The workgroup next in turn after the last full tile also takes the ragged
-//   rest: the partial tile (bounds-checked per vector) and the head and tail
-//   scalars.
+// Work split (done on the host, same for all kernels)
+//   An array of n elements is cut into
+//     head : scalar elements up to the first 128-byte boundary of the array
+//            that steers the split (the output; for dot, `a`)
+//     body : nvec 16-byte vectors (double2 / float4)
+//     tail : the < one-vector remainder.
+//
+// Elementwise kernels: one vector per lane, one wavefront per workgroup
+//   Workgroup g moves vectors 64g .. 64g+63: one contiguous 1 KiB run per
+//   array.  Nothing loops.  The hardware dispatcher hands workgroups out in
+//   index order to whichever wavefront slot frees up, so at any moment the
+//   whole chip works inside one narrow window that slides through each array
+//   (few DRAM pages and TLB entries live at a time), consecutive 1 KiB runs go
+//   to different XCDs, and no software schedule can drift.  Measured on
+//   MI355X this beats every persistent / grid-stride shape tried (256-1024
+//   threads, 1-8 vectors per lane, 1-16 workgroups per CU) by 3-20 %; more
+//   than one vector in flight per lane lowers the bandwidth.
+//   The last workgroup also moves the head and tail scalars.
+//
+// Dot: persistent, one workgroup per compute unit
+//   The body is cut into tiles of blockDim.x * U vectors; workgroup g takes
+//   tiles g, g + G, g + 2G, ...  Lane l of the workgroup reads vectors
+//   l, l + B, ..., l + (U-1)B of a tile, so every wavefront-wide load is one
+//   contiguous 1 KiB run and each lane has 2U independent loads in flight.
+//   Reads alone run fastest with about 32 KiB in flight per compute unit,
+//   which is 256 lanes x 4 vectors x 2 arrays.  The workgroup whose turn comes
+//   after the last full tile also takes the ragged rest.
 //
 // Compile with -ffp-contract=off: Triad must round s*c and then b + (s*c).
 #pragma once
@@ -103,59 +115,35 @@ __device__ __forceinline__ size_t wave_uniform(size_t x) {
   return ((size_t)hi << 32) | lo;
 }
 
-// Elementwise kernel.  out/in0/in1 point at element 0 of the arrays.
-//   head       : scalars before the vector body;  nvec : vectors in the body;
-//   full_tiles : nvec / (blockDim.x * U), computed on the host;
-//   n          : total elements (tail = n - head - nvec*lanes).
+// Elementwise kernel, launched with kWave threads per workgroup and
+// max(1, ceil(nvec / kWave)) workgroups.  out/in0/in1 point at element 0.
+//   head : scalars before the vector body;  nvec : vectors in the body;
+//   n    : total elements (tail = n - head - nvec*lanes < lanes).
 // (out + head) is 16-byte aligned; ALIGNED says (in0 + head) and (in1 + head) are too.
-template <typename T, Op OP, int U, bool ALIGNED, bool NT_LD, bool NT_ST>
-__global__ __launch_bounds__(kMaxBlock) void stream_kernel(
+template <typename T, Op OP, bool ALIGNED, bool NT_LD, bool NT_ST>
+__global__ __launch_bounds__(kWave) void stream_kernel(
     T* __restrict__ out, const T* __restrict__ in0, const T* __restrict__ in1, T s,
-    unsigned head, size_t nvec, size_t full_tiles, size_t n) {
+    unsigned head, size_t nvec, size_t n) {
   typedef typename Vec16<T>::type V;
   constexpr int L = Vec16<T>::lanes;
-  const unsigned B = blockDim.x;
-  const unsigned tid = threadIdx.x;
-  const size_t tile_vecs = (size_t)B * U;
-  const V sv = (V)(s);
+  const unsigned lane = threadIdx.x;
+  const size_t v0 = wave_uniform((size_t)blockIdx.x * kWave);   // first vector of this wavefront
 
-  T* const obody = out + head;
-  const T* const xbody = in0 + head;
-  const T* const ybody = kTwoInputs<OP> ? in1 + head : nullptr;
-
-  for (size_t tile = blockIdx.x; tile < full_tiles; tile += gridDim.x) {
-    const size_t e0 = wave_uniform(tile * tile_vecs * L);   // first element of the tile
-    const T* xp = xbody + e0;
-    const T* yp = kTwoInputs<OP> ? ybody + e0 : nullptr;
-    T* op = obody + e0;
-    V x[U], y[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const unsigned v = (tid + u * B) * L;
-      x[u] = load16<T, ALIGNED, NT_LD>(xp + v);
-      if constexpr (kTwoInputs<OP>) y[u] = load16<T, ALIGNED, NT_LD>(yp + v);
-      else y[u] = x[u];
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const unsigned v = (tid + u * B) * L;
-      store16<T, NT_ST>(op + v, apply<OP, V>(x[u], y[u], sv));
-    }
+  if (v0 + lane < nvec) {
+    const size_t e0 = (size_t)head + v0 * L;
+    const unsigned e = lane * L;
+    const V x = load16<T, ALIGNED, NT_LD>(in0 + e0 + e);
+    V y = x;
+    if constexpr (kTwoInputs<OP>) y = load16<T, ALIGNED, NT_LD>(in1 + e0 + e);
+    store16<T, NT_ST>(out + e0 + e, apply<OP, V>(x, y, (V)(s)));
   }
 
-  // Ragged rest, taken by the workgroup whose turn comes after the last full tile.
-  if (blockIdx.x == ragged_group(full_tiles)) {
-    const size_t v0 = full_tiles * tile_vecs;
-    for (size_t v = v0 + tid; v < nvec; v += B) {
-      const V x = load16<T, ALIGNED, false>(xbody + v * L);
-      V y = x;
-      if constexpr (kTwoInputs<OP>) y = load16<T, ALIGNED, false>(ybody + v * L);
-      store16<T, false>(obody + v * L, apply<OP, V>(x, y, sv));
-    }
+  // Head and tail scalars (fewer than 128/sizeof(T) + lanes <= kWave of them).
+  if (blockIdx.x == gridDim.x - 1) {
     const size_t tail0 = (size_t)head + nvec * L;
-    const unsigned tail = (unsigned)(n - tail0);          // < L
-    if (tid < head + tail) {
-      const size_t i = tid < head ? (size_t)tid : tail0 + (tid - head);
+    const unsigned tail = (unsigned)(n - tail0);
+    if (lane < head + tail) {
+      const size_t i = lane < head ? (size_t)lane : tail0 + (lane - head);
       const T x = in0[i];
       T y = x;
       if constexpr (kTwoInputs<OP>) y = in1[i];

@@ -32,7 +32,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_status_strings():
     seen = set()
-    for st in range(6):
+    for st in range(7):
         msg = opal.opal_status_string(st)
         assert msg and msg not in seen
         seen.add(msg)
