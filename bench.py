@@ -63,7 +63,7 @@ def main():
     ap.add_argument("--workload", default="n2p28_f64", help="name or index of a workload in opal_inputs.WORKLOADS")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing and the result check")
     ap.add_argument("--cpu-steps", type=int, default=2, help="oracle passes to time (the minimum is reported)")
-    ap.add_argument("--skew-bytes", type=int, default=0,
+    ap.add_argument("--skew-bytes", type=int, default=1024,
                     help="extra bytes between the starts of consecutive arrays beyond the array size (the arrays "
                          "are carved out of one allocation at base + k * (array bytes + skew), k = 0, 1, 2)")
     ap.add_argument("--calibration-copy", action="store_true",
