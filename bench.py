@@ -63,6 +63,9 @@ def main():
     ap.add_argument("--workload", default="n2p28_f64", help="name or index of a workload in opal_inputs.WORKLOADS")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing and the result check")
     ap.add_argument("--cpu-steps", type=int, default=2, help="oracle passes to time (the minimum is reported)")
+    ap.add_argument("--n", type=int, default=None, help="override the workload's element count")
+    ap.add_argument("--offset-elems", type=int, default=None,
+                    help="override the workload's misalignment (elements past a 256-byte boundary)")
     ap.add_argument("--skew-bytes", type=int, default=1024,
                     help="extra bytes between the starts of consecutive arrays beyond the array size (the arrays "
                          "are carved out of one allocation at base + k * (array bytes + skew), k = 0, 1, 2)")
@@ -88,6 +91,10 @@ def main():
     opal.load()
 
     wl = oi.workload(int(args.workload) if args.workload.isdigit() else args.workload)
+    if args.n is not None or args.offset_elems is not None:
+        import dataclasses
+        wl = dataclasses.replace(wl, name=wl.name + "_custom", n=wl.n if args.n is None else args.n,
+                                 offset_elems=wl.offset_elems if args.offset_elems is None else args.offset_elems)
     n, item = wl.n, wl.itemsize
     dt = opal.OPAL_F64 if wl.dtype == "f64" else opal.OPAL_F32
     tdt = torch.float64 if wl.dtype == "f64" else torch.float32
