@@ -55,6 +55,126 @@ def measured_traffic(workload_name, kernel):
     return rec.get("workloads", {}).get(workload_name, {}).get(kernel)
 
 
+def paper_shapes(args):
+    """The paper's own workload shapes for these kernels (Table 1: ARRAY_SIZE in {2000896, 4000768,
+    6000640}, num_times in {100, 200, 300}): 16-48 MB arrays that sit in the 256 MB Infinity Cache, where a
+    kernel lasts a few microseconds and the launch path decides the run time (the regime of the paper's
+    Section 6.4 finding).  One iteration = copy, scale, add, triad, dot.  Three ways to issue the
+    iterations through the same C ABI are timed wall-clock, synchronisation to synchronisation:
+      eager     : num_times x 5 asynchronous calls, one synchronisation at the end
+      graph     : one iteration captured into a HIP graph, replayed num_times
+      graph_all : all num_times iterations captured into one HIP graph, launched once
+    Prints one JSON line."""
+    import numpy as np
+    import torch
+
+    import opal_inputs as oi
+    import paper_2510_00932_amd as opal
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the kernels have no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    opal.load()
+    dev = torch.device("cuda:0")
+    wl = oi.workload(0)
+    dt, tdt, item, s = opal.OPAL_F64, torch.float64, 8, wl.s
+    results = []
+    checks = []
+    for n in (2000896, 4000768, 6000640):
+        host = oi.make_arrays(wl, n=n)
+        pitch = (n * item + 255) // 256 * 256 + args.skew_bytes
+        pool = torch.empty(3 * pitch + 256, dtype=torch.uint8, device=dev)
+        a, b, c = (pool[k * pitch:k * pitch + n * item].view(tdt) for k in range(3))
+        ws_bytes = opal.opal_dot_workspace_bytes(n, dt)
+        ws = torch.empty(ws_bytes // 8, dtype=torch.float64, device=dev)
+        res = torch.empty(1, dtype=torch.float64, device=dev)
+        stream = torch.cuda.Stream()
+        pa, pb, pc, pws, pres = a.data_ptr(), b.data_ptr(), c.data_ptr(), ws.data_ptr(), res.data_ptr()
+
+        def reset():
+            for d, h in zip((a, b, c), host):
+                d.copy_(torch.from_numpy(h))
+            torch.cuda.synchronize()
+
+        def iteration(st):
+            opal.opal_copy(pa, pc, n, dt, st)
+            opal.opal_scale(pb, pc, s, n, dt, st)
+            opal.opal_add(pa, pb, pc, n, dt, st)
+            opal.opal_triad(pa, pb, pc, s, n, dt, st)
+            opal.opal_dot(pa, pb, n, dt, pws, ws_bytes, pres, st)
+
+        reset()
+        iteration(stream)
+        stream.synchronize()
+        g1 = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g1, stream=stream):
+            iteration(torch.cuda.current_stream())
+        bytes_per_iter = 96 * n
+        for num_times in (100, 200, 300):
+            row = {"array_size": n, "num_times": num_times}
+            # eager
+            reset()
+            t0 = time.perf_counter()
+            for _ in range(num_times):
+                iteration(stream)
+            stream.synchronize()
+            t = time.perf_counter() - t0
+            row["eager_us_per_iter"] = round(t / num_times * 1e6, 2)
+            final_eager = (a.cpu().numpy(), b.cpu().numpy(), c.cpu().numpy(), float(res.item()))
+            # graph of one iteration, replayed
+            reset()
+            t0 = time.perf_counter()
+            for _ in range(num_times):
+                g1.replay()
+            torch.cuda.synchronize()
+            t = time.perf_counter() - t0
+            row["graph_us_per_iter"] = round(t / num_times * 1e6, 2)
+            final_graph = (a.cpu().numpy(), b.cpu().numpy(), c.cpu().numpy(), float(res.item()))
+            # one graph holding every iteration
+            gall = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gall, stream=stream):
+                for _ in range(num_times):
+                    iteration(torch.cuda.current_stream())
+            reset()
+            t0 = time.perf_counter()
+            gall.replay()
+            torch.cuda.synchronize()
+            t = time.perf_counter() - t0
+            row["graph_all_us_per_iter"] = round(t / num_times * 1e6, 2)
+            final_all = (a.cpu().numpy(), b.cpu().numpy(), c.cpu().numpy(), float(res.item()))
+            del gall
+            best = min(row["eager_us_per_iter"], row["graph_us_per_iter"], row["graph_all_us_per_iter"])
+            row["best_GBps"] = round(bytes_per_iter / best / 1e3, 1)
+            same = all(np.array_equal(x.view(np.uint64), y.view(np.uint64)) and np.array_equal(x.view(np.uint64), z.view(np.uint64))
+                       for x, y, z in zip(final_eager[:3], final_graph[:3], final_all[:3]))
+            row["three_ways_bit_identical"] = bool(same and final_eager[3] == final_graph[3] == final_all[3])
+            if num_times == 100 and not args.no_cpu_baseline:
+                import oracle
+                xa, xb, xc = (h.copy() for h in host)
+                r = 0.0
+                for _ in range(num_times):
+                    oracle.copy(xa, xc)
+                    oracle.scale(xb, xc, s)
+                    oracle.add(xa, xb, xc)
+                    oracle.triad(xa, xb, xc, s)
+                    r = oracle.dot(xa, xb)
+                exact = all(np.array_equal(x.view(np.uint64), y.view(np.uint64)) for x, y in zip(final_eager[:3], (xa, xb, xc)))
+                rel = abs(final_eager[3] - r) / abs(r)
+                checks.append({"array_size": n, "num_times": num_times, "elementwise_bit_exact": bool(exact),
+                               "dot_rel_err": float("%.3e" % rel)})
+            results.append(row)
+        del g1
+    out = {"metric": "time per iteration (copy, scale, add, triad, dot) at the paper's array sizes, 1 GPU",
+           "unit": "us", "dtype": "f64", "data": "synthetic", "bytes_per_iteration": "96 * array_size",
+           "results": results, "check_vs_oracle": checks}
+    print(json.dumps(out))
+    bad = [r for r in results if not r["three_ways_bit_identical"]] + \
+        [c for c in checks if not (c["elementwise_bit_exact"] and c["dot_rel_err"] <= 1e-12)]
+    if bad:
+        print("bench.py: paper-shape results differ", file=sys.stderr)
+        sys.exit(1)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -69,6 +189,9 @@ def main():
     ap.add_argument("--skew-bytes", type=int, default=1024,
                     help="extra bytes between the starts of consecutive arrays beyond the array size (the arrays "
                          "are carved out of one allocation at base + k * (array bytes + skew), k = 0, 1, 2)")
+    ap.add_argument("--paper-shapes", action="store_true",
+                    help="instead of the roofline benchmark, time the paper's own (small, cache-resident) array "
+                         "sizes and repetition counts issued eagerly and through HIP graphs")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain torch copy of 1 GiB (a kernel of known traffic, for scaling "
                          "FETCH_SIZE / WRITE_SIZE counter readings)")
@@ -78,6 +201,10 @@ def main():
         print("bench.py: this path is single-GPU by construction (no sharding, no collectives); "
               "run it with --gpus 1", file=sys.stderr)
         sys.exit(2)
+
+    if args.paper_shapes:
+        paper_shapes(args)
+        return
 
     import numpy as np
     import torch
@@ -183,7 +310,11 @@ def main():
             "GBps_median": round(nbytes / med / 1e6, 1),
             "frac_of_peak_avg": round(nbytes / avg / 1e6 / HBM_PEAK_GBS, 4),
         }
-    dominant = max(KERNELS, key=lambda name: kernels[name]["avg_us"])
+    # The kernel with the largest share of the step; add and triad move the same bytes and tie to
+    # within noise, so a tie (1 %) goes to triad, which also does the most arithmetic.
+    longest = max(kernels[name]["avg_us"] for name in KERNELS)
+    dominant = "triad" if kernels["triad"]["avg_us"] >= 0.99 * longest else \
+        max(KERNELS, key=lambda name: kernels[name]["avg_us"])
     dk = kernels[dominant]
     roofline = {
         "kernel": dominant, "bound": "hbm", "achieved": dk["GBps_avg"], "peak": HBM_PEAK_GBS, "unit": "GB/s",

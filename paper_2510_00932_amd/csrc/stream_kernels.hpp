@@ -22,6 +22,10 @@
 //   threads, 1-8 vectors per lane, 1-16 workgroups per CU) by 3-20 %; more
 //   than one vector in flight per lane lowers the bandwidth.
 //   The last workgroup also moves the head and tail scalars.
+//   Arrays small enough to stay in the 256 MB Infinity Cache from one kernel to
+//   the next (a few million elements: the regime where the dispatch rate of
+//   wave-sized workgroups, about 4.7 per ns, becomes the floor) use the same
+//   kernel with 256 lanes per workgroup and without the non-temporal hint.
 //
 // Dot: persistent, one workgroup per compute unit
 //   The body is cut into tiles of blockDim.x * U vectors; workgroup g takes
@@ -115,27 +119,32 @@ __device__ __forceinline__ size_t wave_uniform(size_t x) {
   return ((size_t)hi << 32) | lo;
 }
 
-// Elementwise kernel, launched with kWave threads per workgroup and
-// max(1, ceil(nvec / kWave)) workgroups.  out/in0/in1 point at element 0.
+// Elementwise kernel, launched with BLOCK threads per workgroup and
+// max(1, ceil(nvec / BLOCK)) workgroups; lane l of workgroup g moves vector
+// g * BLOCK + l.  out/in0/in1 point at element 0.
 //   head : scalars before the vector body;  nvec : vectors in the body;
 //   n    : total elements (tail = n - head - nvec*lanes < lanes).
 // (out + head) is 16-byte aligned; ALIGNED says (in0 + head) and (in1 + head) are too.
-template <typename T, Op OP, bool ALIGNED, bool NT_LD, bool NT_ST>
-__global__ __launch_bounds__(kWave) void stream_kernel(
+// NT: loads and stores carry the non-temporal hint (arrays that are streamed
+// from and to HBM); without it lines stay in L2 / Infinity Cache for the next
+// kernel (arrays small enough to live there).
+template <typename T, Op OP, int BLOCK, bool ALIGNED, bool NT>
+__global__ __launch_bounds__(BLOCK) void stream_kernel(
     T* __restrict__ out, const T* __restrict__ in0, const T* __restrict__ in1, T s,
     unsigned head, size_t nvec, size_t n) {
   typedef typename Vec16<T>::type V;
   constexpr int L = Vec16<T>::lanes;
+  static_assert(BLOCK % kWave == 0 && BLOCK >= kWave, "whole wavefronts");
   const unsigned lane = threadIdx.x;
-  const size_t v0 = wave_uniform((size_t)blockIdx.x * kWave);   // first vector of this wavefront
+  const size_t v0 = wave_uniform((size_t)blockIdx.x * BLOCK);   // first vector of this workgroup
 
   if (v0 + lane < nvec) {
     const size_t e0 = (size_t)head + v0 * L;
     const unsigned e = lane * L;
-    const V x = load16<T, ALIGNED, NT_LD>(in0 + e0 + e);
+    const V x = load16<T, ALIGNED, NT>(in0 + e0 + e);
     V y = x;
-    if constexpr (kTwoInputs<OP>) y = load16<T, ALIGNED, NT_LD>(in1 + e0 + e);
-    store16<T, NT_ST>(out + e0 + e, apply<OP, V>(x, y, (V)(s)));
+    if constexpr (kTwoInputs<OP>) y = load16<T, ALIGNED, NT>(in1 + e0 + e);
+    store16<T, NT>(out + e0 + e, apply<OP, V>(x, y, (V)(s)));
   }
 
   // Head and tail scalars (fewer than 128/sizeof(T) + lanes <= kWave of them).

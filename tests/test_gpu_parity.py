@@ -19,7 +19,9 @@ DTYPES = [np.float64, np.float32]
 SMALL_SIZES = [0, 1, 2, 3, 4, 5, 7, 8, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257,
                511, 512, 513, 1023, 1024, 1025, 2047, 2048, 2049, 4095, 4096, 4097, 8191, 8192, 8193]
 MID_SIZES = [65535, 65536, 65537, (1 << 20) - 1, (1 << 20) + 1, 1572869]
-LARGE_SIZES = [(1 << 22) - 1, (1 << 22) + 1, (1 << 23) + 2049, (1 << 24) + 12345, 3 * (1 << 23) + 7]
+# ... and both sides of the array size (96 MiB) at which the library switches from cache-friendly to streaming accesses
+LARGE_SIZES = [(1 << 22) - 1, (1 << 22) + 1, (1 << 23) + 2049, 3 * (1 << 22) - 1, 3 * (1 << 22) + 1,
+               (1 << 24) + 12345, 3 * (1 << 23) - 1, 3 * (1 << 23) + 7]
 OFFSETS = [(0, 0, 0), (1, 1, 1), (1, 0, 0), (0, 1, 0), (0, 0, 1), (3, 2, 1), (1, 2, 3), (5, 5, 5)]
 
 
@@ -97,7 +99,8 @@ def test_size_and_alignment_sweep(parity, dtype):
 def test_large_ragged_sizes(parity, dtype):
     w = oi.workload(4)
     full = [oi.uniform_array(w.seed, k, max(LARGE_SIZES), dtype, w.lo, w.hi) for k in range(3)]
-    for n, offsets in zip(LARGE_SIZES, [(0, 0, 0), (1, 1, 1), (1, 0, 2), (0, 0, 0), (3, 3, 3)]):
+    for n, offsets in zip(LARGE_SIZES, [(0, 0, 0), (1, 1, 1), (1, 0, 2), (0, 0, 0), (1, 1, 1), (0, 0, 0), (3, 3, 3),
+                                        (2, 0, 1)]):
         parity.run_chain([x[:n].copy() for x in full], w.s, offsets)
         parity.run_fresh([x[:n].copy() for x in full], w.s, offsets)
 
@@ -192,3 +195,67 @@ def test_against_torch_as_a_sanity_check(harness):
     assert torch.equal(out, c * w.s)
     r = harness.dot_device(a.data_ptr(), b.data_ptr(), n, opal.OPAL_F64)
     assert abs(r - torch.dot(a, b).item()) <= 1e-9 * n
+
+
+# ------------------------------------------------------------------ captured into a HIP graph
+
+def test_graph_replay_matches_oracle(parity, harness):
+    """The library neither allocates nor synchronises, so one pass copy -> scale -> add -> triad -> dot
+    can be captured into a HIP graph.  Every replay (with the program's own eager launches and
+    synchronisations in between) must leave exactly what that many oracle passes leave."""
+    import oracle
+    w = oi.workload(0)
+    n = 2000896 + 3                                   # an array size of the paper's Table 1, plus a ragged tail
+    ha, hb, hc = oi.make_arrays(w, n=n)
+    a, b, c = (harness.GuardedArray(n, np.float64, off).upload(x) for x, off in zip((ha, hb, hc), (0, 1, 0)))
+    dt = opal.OPAL_F64
+    ws_bytes = opal.opal_dot_workspace_bytes(n, dt)
+    ws = torch.zeros(ws_bytes // 8, dtype=torch.float64, device="cuda:0")
+    res = torch.zeros(1, dtype=torch.float64, device="cuda:0")
+    # eager scratch work that runs between the replays
+    ea = harness.GuardedArray(4099, np.float64).upload(np.full(4099, 2.0))
+    eb = harness.GuardedArray(4099, np.float64).upload(np.full(4099, 3.0))
+    ec = harness.GuardedArray(4099, np.float64).upload(np.zeros(4099))
+
+    def one_pass(stream):
+        opal.opal_copy(a.ptr, c.ptr, n, dt, stream)
+        opal.opal_scale(b.ptr, c.ptr, w.s, n, dt, stream)
+        opal.opal_add(a.ptr, b.ptr, c.ptr, n, dt, stream)
+        opal.opal_triad(a.ptr, b.ptr, c.ptr, w.s, n, dt, stream)
+        opal.opal_dot(a.ptr, b.ptr, n, dt, ws.data_ptr(), ws_bytes, res.data_ptr(), stream)
+
+    def oracle_pass():
+        oracle.copy(ha, hc)
+        oracle.scale(hb, hc, w.s)
+        oracle.add(ha, hb, hc)
+        oracle.triad(ha, hb, hc, w.s)
+        return oracle.dot(ha, hb)
+
+    def check(what, want_dot):
+        torch.cuda.synchronize()
+        for name, d, h in (("a", a, ha), ("b", b, hb), ("c", c, hc)):
+            parity.assert_same_bits(d, h, "%s, array %s" % (what, name))
+            assert d.guards_intact()
+        got = float(res.item())
+        assert abs(got - want_dot) <= 1e-12 * abs(want_dot), (what, got, want_dot)
+
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    one_pass(side)                                    # eager pass (also warms the library's device query)
+    side.synchronize()
+    check("eager pass", oracle_pass())
+
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        one_pass(torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    check("after capture (capturing must not execute)", oracle.dot(ha, hb))
+
+    for k in range(5):
+        graph.replay()
+        check("replay %d" % k, oracle_pass())
+        opal.opal_add(ea.ptr, eb.ptr, ec.ptr, 4099, dt, None)      # eager work between replays
+        torch.cuda.synchronize()
+        assert (ec.download() == 5.0).all()
+        res.fill_(float("nan"))
+        torch.cuda.synchronize()
