@@ -40,6 +40,8 @@ def _lib():
             getattr(lib, "oracle_dot_plain_" + suf).restype = dbl
             getattr(lib, "oracle_dot_abs_" + suf).argtypes = [vp, vp, sz]
             getattr(lib, "oracle_dot_abs_" + suf).restype = dbl
+            getattr(lib, "oracle_lds_stream_" + suf).argtypes = [vp, vp, dbl, sz, ctypes.c_uint]
+            getattr(lib, "oracle_lds_stream_" + suf).restype = ctypes.c_int
         _LIB = lib
     return _LIB
 
@@ -109,3 +111,10 @@ def dot_abs(a, b):
     """sum_i |a[i]*b[i]| in long double, as double (for condition numbers)."""
     suf, n = _chk(a, b)
     return getattr(_lib(), "oracle_dot_abs_" + suf)(_p(a), _p(b), n)
+
+
+def lds_stream(inp, out, c, rep):
+    """Tile-wise (1024 16-byte vectors per tile): rep rounds of x'[j] = x[(j+1) mod 1024] + c."""
+    suf, n = _chk(inp, out)
+    if getattr(_lib(), "oracle_lds_stream_" + suf)(_p(inp), _p(out), float(c), n, int(rep)) != 0:
+        raise ValueError("n must be a whole number of tiles of 1024 16-byte vectors")

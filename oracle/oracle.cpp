@@ -22,10 +22,14 @@
 //   triad: a[i] = b[i] + s * c[i]     (multiply rounded, then add rounded)
 //   dot  : sum_i a[i] * b[i]
 //
-// Parity pins for every function here live in tests/test_oracle_pins.py:
-// closed forms on constant and ramp fills, exact rational arithmetic on small
-// random inputs, a vector on which fused and unfused Triad differ, and a
-// dyadic chain whose every step is exact.
+// Also here: the LDS-streaming microkernel (the analogue of the shared-memory
+// benchmark subject of Table 1), defined further down.
+//
+// Parity pins for every function here live in tests/test_oracle_pins.py and
+// tests/test_oracle_lds_pins.py: closed forms on constant and ramp fills,
+// exact rational arithmetic on small random inputs, a vector on which fused
+// and unfused Triad differ, a dyadic chain whose every step is exact, and for
+// the LDS kernel pure rotations, exact adds and composition of calls.
 
 #include <cstddef>
 #include <cstdint>
@@ -102,6 +106,37 @@ long double dot_abs_loop(const T* a, const T* b, size_t n) {
   return sum;
 }
 
+// LDS streaming microkernel (the library's own definition of the shared-memory
+// benchmark subject of Table 1; the paper gives none).  Arrays are cut into
+// tiles of 1024 16-byte vectors; `per_vec` = elements per vector (2 for double,
+// 4 for float).  One round: x'[j] = x[(j + 1) mod 1024] + c on whole vectors,
+// i.e. every element moves one vector down and gets c added once (one rounded
+// add).  `rep` rounds, done literally, round by round, on a scratch copy of
+// the tile.  n must be a whole number of tiles (returns -1 otherwise).
+template <typename T>
+int lds_stream_loop(const T* in, T* out, T c, size_t n, unsigned rep) {
+  const size_t tile_vecs = 1024;
+  const size_t per_vec = 16 / sizeof(T);
+  const size_t tile = tile_vecs * per_vec;
+  if (n % tile != 0) return -1;
+  T* cur = new T[tile];
+  T* next = new T[tile];
+  for (size_t t0 = 0; t0 < n; t0 += tile) {
+    for (size_t e = 0; e < tile; ++e) cur[e] = in[t0 + e];
+    for (unsigned r = 0; r < rep; ++r) {
+      for (size_t j = 0; j < tile_vecs; ++j) {
+        const size_t src = (j + 1) % tile_vecs;
+        for (size_t l = 0; l < per_vec; ++l) next[j * per_vec + l] = cur[src * per_vec + l] + c;
+      }
+      T* tmp = cur; cur = next; next = tmp;
+    }
+    for (size_t e = 0; e < tile; ++e) out[t0 + e] = cur[e];
+  }
+  delete[] cur;
+  delete[] next;
+  return 0;
+}
+
 }  // namespace
 
 extern "C" {
@@ -145,6 +180,13 @@ double oracle_dot_plain_f32(const float* a, const float* b, size_t n) {
 }
 double oracle_dot_abs_f32(const float* a, const float* b, size_t n) {
   return (double)dot_abs_loop(a, b, n);
+}
+
+int oracle_lds_stream_f64(const double* in, double* out, double c, size_t n, unsigned rep) {
+  return lds_stream_loop(in, out, c, n, rep);
+}
+int oracle_lds_stream_f32(const float* in, float* out, double c, size_t n, unsigned rep) {
+  return lds_stream_loop(in, out, (float)c, n, rep);
 }
 
 }  // extern "C"
