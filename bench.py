@@ -175,6 +175,75 @@ def paper_shapes(args):
         sys.exit(1)
 
 
+def lds_bench(args):
+    """LDS-streaming microkernel (the analogue of the shared-memory benchmark subject of the paper's
+    Table 1, rep = 300..1500, default 600): achieved LDS bandwidth = 32 bytes per 16-byte vector per
+    round / time.  Peak used: 256 compute units x 128 bytes per clock x 2.4 GHz = 78.6 TB/s (derived
+    from unit counts and clock, not a published figure).  Prints one JSON line."""
+    import numpy as np
+    import torch
+
+    import opal_inputs as oi
+    import paper_2510_00932_amd as opal
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the kernels have no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    opal.load()
+    peak = 256 * 128 * 2.4e9 / 1e9
+    results = []
+    checks = []
+    stream = torch.cuda.Stream()
+    for dtype_name, dt, tdt, npdt in (("f32", opal.OPAL_F32, torch.float32, np.float32),
+                                      ("f64", opal.OPAL_F64, torch.float64, np.float64)):
+        te = opal.opal_lds_tile_elements(dt)
+        tiles = 256 * 5 * 8                     # eight full waves of resident workgroups (5 per compute unit)
+        n = tiles * te
+        host = oi.uniform_array(42, 0, n, npdt, 0.5, 1.5)
+        x = torch.from_numpy(host).cuda()
+        y = torch.empty_like(x)
+        torch.cuda.synchronize()
+        for rep in (300, 600, 900, 1200, 1500):
+            for _ in range(2):
+                opal.opal_lds_stream(x, y, 0.4, n, rep, dt, stream)
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+            for e0, e1 in ev:
+                e0.record(stream)
+                opal.opal_lds_stream(x, y, 0.4, n, rep, dt, stream)
+                e1.record(stream)
+            stream.synchronize()
+            ms = sorted(e0.elapsed_time(e1) for e0, e1 in ev)
+            avg = sum(ms) / len(ms)
+            lds_bytes = 32.0 * (n * x.element_size() / 16) * rep
+            results.append({"dtype": dtype_name, "n": n, "rep": rep, "avg_us": round(avg * 1e3, 1),
+                            "min_us": round(ms[0] * 1e3, 1), "lds_GBps_avg": round(lds_bytes / avg / 1e6, 0),
+                            "frac_of_lds_peak": round(lds_bytes / avg / 1e6 / peak, 4)})
+        if not args.no_cpu_baseline:
+            import oracle
+            m = 64 * te
+            want = np.zeros(m, npdt)
+            t0 = time.perf_counter()
+            oracle.lds_stream(host[:m].copy(), want, 0.4, 600)
+            t_cpu = time.perf_counter() - t0
+            got = torch.empty(m, dtype=tdt, device="cuda")
+            opal.opal_lds_stream(x[:m], got, 0.4, m, 600, dt, stream)
+            stream.synchronize()
+            bits = np.uint64 if dtype_name == "f64" else np.uint32
+            checks.append({"dtype": dtype_name, "n": m, "rep": 600,
+                           "bit_exact": bool(np.array_equal(got.cpu().numpy().view(bits), want.view(bits))),
+                           "oracle_GBps": round(32.0 * (m * host.itemsize / 16) * 600 / t_cpu / 1e9, 2)})
+    out = {"metric": "achieved LDS GB/s of the LDS-streaming microkernel, 1 GPU", "unit": "GB/s", "n_gpus": 1,
+           "steps": args.steps, "data": "synthetic", "peak_GBps": peak,
+           "roofline": {"bound": "lds", "peak": peak, "unit": "GB/s",
+                        "achieved": max(r["lds_GBps_avg"] for r in results),
+                        "frac": max(r["frac_of_lds_peak"] for r in results)},
+           "results": results, "cpu_baseline": {"kind": "oracle", "cores": 1, "checks": checks}}
+    print(json.dumps(out))
+    if any(not c["bit_exact"] for c in checks):
+        print("bench.py: LDS kernel differs from the oracle", file=sys.stderr)
+        sys.exit(1)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -192,6 +261,8 @@ def main():
     ap.add_argument("--paper-shapes", action="store_true",
                     help="instead of the roofline benchmark, time the paper's own (small, cache-resident) array "
                          "sizes and repetition counts issued eagerly and through HIP graphs")
+    ap.add_argument("--lds", action="store_true",
+                    help="instead of the roofline benchmark, time the LDS-streaming microkernel (rep = 300..1500)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain torch copy of 1 GiB (a kernel of known traffic, for scaling "
                          "FETCH_SIZE / WRITE_SIZE counter readings)")
@@ -204,6 +275,9 @@ def main():
 
     if args.paper_shapes:
         paper_shapes(args)
+        return
+    if args.lds:
+        lds_bench(args)
         return
 
     import numpy as np

@@ -47,7 +47,7 @@ enum {
   OPAL_ERR_ALIGN = 3,     /* a pointer is not a multiple of its element size (workspace/result: 8) */
   OPAL_ERR_WORKSPACE = 4, /* workspace_bytes < opal_dot_workspace_bytes(n, dtype) */
   OPAL_ERR_LAUNCH = 5,    /* the HIP runtime refused a query or a kernel launch */
-  OPAL_ERR_SIZE = 6       /* n needs more than 2^31 - 1 workgroups (n >= 2^37 vectors' worth) */
+  OPAL_ERR_SIZE = 6       /* n needs more than 2^31 - 1 workgroups, or is not a whole number of LDS tiles */
 };
 
 /* Element types (passed as int). */
@@ -87,6 +87,25 @@ size_t opal_dot_workspace_bytes(size_t n, int dtype);
  * Calls that share a workspace must be ordered (same stream, or synchronised). */
 int opal_dot(const void* a, const void* b, size_t n, int dtype,
              void* workspace, size_t workspace_bytes, double* result, void* stream);
+
+/* LDS streaming microkernel: the analogue, for this chip's 160 KiB local data share, of the
+ * shared-memory benchmark the paper lists beside the five kernels (Table 1: "Shmembench",
+ * parameter rep = kernel repetition count, 300..1500, default 600; Section 5.2: "shared-memory
+ * operations").  The paper gives no definition, so this one is the library's own:
+ *
+ *   The arrays are cut into tiles of OPAL_LDS_TILE_VECTORS (1024) 16-byte vectors (2048 fp64
+ *   or 4096 fp32 elements).  A tile is loaded into the LDS and then goes through `rep` rounds;
+ *   in one round every vector j of the tile becomes  x'[j] = x[(j + 1) mod 1024] + c  (the
+ *   tile rotates by one vector and c is added to every element, one rounded add), each round
+ *   reading what the previous one wrote through the LDS.  After the last round the tile is
+ *   stored to `out`.  So  out = rotate_by_rep(in) with c added rep times, tile by tile.
+ *
+ * in: device, read, n elements; out: device, written, n elements, must not overlap in.  Both
+ * 16-byte aligned (else OPAL_ERR_ALIGN).  n must be a multiple of opal_lds_tile_elements(dtype)
+ * (else OPAL_ERR_SIZE).  rep = 0 copies.  LDS traffic: 32 bytes per vector per round. */
+#define OPAL_LDS_TILE_VECTORS 1024
+size_t opal_lds_tile_elements(int dtype);   /* 2048 (fp64), 4096 (fp32), 0 for an unknown dtype */
+int opal_lds_stream(const void* in, void* out, double c, size_t n, unsigned rep, int dtype, void* stream);
 
 /* Static, NUL-terminated description of a status code (never NULL). */
 const char* opal_status_string(int status);

@@ -20,6 +20,8 @@ from .binding import (  # noqa: F401
     opal_copy,
     opal_dot,
     opal_dot_workspace_bytes,
+    opal_lds_stream,
+    opal_lds_tile_elements,
     opal_scale,
     opal_status_string,
     opal_triad,

@@ -60,6 +60,10 @@ def load():
     lib.opal_dot_workspace_bytes.restype = sz
     lib.opal_status_string.argtypes = [it]
     lib.opal_status_string.restype = ctypes.c_char_p
+    lib.opal_lds_tile_elements.argtypes = [it]
+    lib.opal_lds_tile_elements.restype = sz
+    lib.opal_lds_stream.argtypes = [vp, vp, dbl, sz, ctypes.c_uint, it, vp]
+    lib.opal_lds_stream.restype = it
     lib.opal_last_hip_error.argtypes = []
     lib.opal_last_hip_error.restype = ctypes.c_char_p
     lib.opal_bytes_per_element.argtypes = [it, it]
@@ -147,3 +151,12 @@ def opal_dot(a, b, n, dtype, workspace, workspace_bytes, result, stream=None):
     """result[0] = sum a[i]*b[i] (result: one fp64 in device memory)."""
     _check(load().opal_dot(_ptr(a), _ptr(b), n, _dtype_of(a, dtype), _ptr(workspace), workspace_bytes,
                            _ptr(result), _stream(stream)))
+
+
+def opal_lds_tile_elements(dtype) -> int:
+    return int(load().opal_lds_tile_elements(int(dtype)))
+
+
+def opal_lds_stream(inp, out, c, n, rep, dtype=None, stream=None):
+    """Tile-wise: rotate by one 16-byte vector and add c, rep times, through the LDS."""
+    _check(load().opal_lds_stream(_ptr(inp), _ptr(out), float(c), n, int(rep), _dtype_of(inp, dtype), _stream(stream)))

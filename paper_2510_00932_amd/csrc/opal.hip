@@ -7,6 +7,7 @@
 //         -Xclang -target-feature -Xclang -packed-fp32-ops -shared -fPIC
 
 #include "../../include/opal.h"
+#include "lds_kernel.hpp"
 #include "stream_kernels.hpp"
 
 namespace {
@@ -182,6 +183,18 @@ int launch_dot(const T* a, const T* b, size_t n, double* partials, double* resul
   return launch(dot_final_kernel, 1u, kFinalBlock, stream, cpartials, groups, result) ? OPAL_OK : OPAL_ERR_LAUNCH;
 }
 
+constexpr int kLdsBlock = 256;   // 4 vectors per thread; 32 KiB of LDS per workgroup, 5 workgroups per CU
+
+template <typename T>
+int launch_lds(const T* in, T* out, T c, size_t n, unsigned rep, hipStream_t stream) {
+  const size_t tile = (size_t)kLdsTileVectors * (16 / sizeof(T));
+  const size_t tiles = n / tile;
+  if (tiles > kMaxGrid) return OPAL_ERR_SIZE;
+  return launch(lds_stream_kernel<T, kLdsBlock>, (unsigned)tiles, (unsigned)kLdsBlock, stream, in, out, c, rep)
+             ? OPAL_OK
+             : OPAL_ERR_LAUNCH;
+}
+
 }  // namespace
 
 extern "C" {
@@ -226,6 +239,24 @@ int opal_dot(const void* a, const void* b, size_t n, int dtype, void* workspace,
   return launch_dot<float>(static_cast<const float*>(a), static_cast<const float*>(b), n, partials, result, hs);
 }
 
+size_t opal_lds_tile_elements(int dtype) {
+  if (dtype == OPAL_F64) return (size_t)kLdsTileVectors * 2;
+  if (dtype == OPAL_F32) return (size_t)kLdsTileVectors * 4;
+  return 0;
+}
+
+int opal_lds_stream(const void* in, void* out, double c, size_t n, unsigned rep, int dtype, void* stream) {
+  if (dtype != OPAL_F64 && dtype != OPAL_F32) return OPAL_ERR_DTYPE;
+  if (n == 0) return OPAL_OK;
+  if (in == nullptr || out == nullptr) return OPAL_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(in) % 16 != 0 || reinterpret_cast<uintptr_t>(out) % 16 != 0) return OPAL_ERR_ALIGN;
+  if (n % opal_lds_tile_elements(dtype) != 0) return OPAL_ERR_SIZE;
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  if (dtype == OPAL_F64)
+    return launch_lds<double>(static_cast<const double*>(in), static_cast<double*>(out), c, n, rep, hs);
+  return launch_lds<float>(static_cast<const float*>(in), static_cast<float*>(out), (float)c, n, rep, hs);
+}
+
 const char* opal_status_string(int status) {
   switch (status) {
     case OPAL_OK: return "ok";
@@ -234,7 +265,7 @@ const char* opal_status_string(int status) {
     case OPAL_ERR_ALIGN: return "a pointer is not aligned to its element size";
     case OPAL_ERR_WORKSPACE: return "dot workspace is smaller than opal_dot_workspace_bytes(n, dtype)";
     case OPAL_ERR_LAUNCH: return "the HIP runtime refused a query or a kernel launch";
-    case OPAL_ERR_SIZE: return "n is larger than one launch can cover";
+    case OPAL_ERR_SIZE: return "n is larger than one launch can cover, or not a whole number of LDS tiles";
     default: return "unknown status";
   }
 }
