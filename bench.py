@@ -253,8 +253,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing and the result check")
     ap.add_argument("--cpu-steps", type=int, default=2, help="oracle passes to time (the minimum is reported)")
     ap.add_argument("--n", type=int, default=None, help="override the workload's element count")
-    ap.add_argument("--offset-elems", type=int, default=None,
-                    help="override the workload's misalignment (elements past a 256-byte boundary)")
+    ap.add_argument("--offset-elems", type=str, default=None,
+                    help="override the workload's misalignment (elements past a 256-byte boundary): one number "
+                         "for all three arrays, or a,b,c for one each")
     ap.add_argument("--skew-bytes", type=int, default=1024,
                     help="extra bytes between the starts of consecutive arrays beyond the array size (the arrays "
                          "are carved out of one allocation at base + k * (array bytes + skew), k = 0, 1, 2)")
@@ -292,10 +293,19 @@ def main():
     opal.load()
 
     wl = oi.workload(int(args.workload) if args.workload.isdigit() else args.workload)
-    if args.n is not None or args.offset_elems is not None:
+    offsets = None
+    if args.offset_elems is not None:
+        offsets = [int(x) for x in args.offset_elems.split(",")]
+        offsets = offsets * 3 if len(offsets) == 1 else offsets
+        if len(offsets) != 3 or min(offsets) < 0:
+            print("bench.py: --offset-elems takes one or three non-negative integers", file=sys.stderr)
+            sys.exit(2)
+    if args.n is not None or offsets is not None:
         import dataclasses
         wl = dataclasses.replace(wl, name=wl.name + "_custom", n=wl.n if args.n is None else args.n,
-                                 offset_elems=wl.offset_elems if args.offset_elems is None else args.offset_elems)
+                                 offset_elems=wl.offset_elems if offsets is None else max(offsets))
+    if offsets is None:
+        offsets = [wl.offset_elems] * 3
     n, item = wl.n, wl.itemsize
     dt = opal.OPAL_F64 if wl.dtype == "f64" else opal.OPAL_F32
     tdt = torch.float64 if wl.dtype == "f64" else torch.float32
@@ -310,7 +320,7 @@ def main():
     pitch = ((n + off) * item + 255) // 256 * 256 + args.skew_bytes      # bytes from one array's base to the next
     pool = torch.empty(3 * pitch + 256, dtype=torch.uint8, device=dev)
     assert pool.data_ptr() % 256 == 0
-    a, b, c = (pool[k * pitch + off * item:k * pitch + (off + n) * item].view(tdt) for k in range(3))
+    a, b, c = (pool[k * pitch + o * item:k * pitch + (o + n) * item].view(tdt) for k, o in zip(range(3), offsets))
     for d, h in zip((a, b, c), host):
         d.copy_(torch.from_numpy(h))
     ws_bytes = opal.opal_dot_workspace_bytes(n, dt)
@@ -406,7 +416,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "n": n, "elem_bytes": item, "scalar": s,
-                   "offset_elems": off, "array_pitch_bytes": pitch, "seed": wl.seed, "value_range": [wl.lo, wl.hi],
+                   "offset_elems": offsets, "array_pitch_bytes": pitch, "seed": wl.seed, "value_range": [wl.lo, wl.hi],
                    "step": "copy,scale,add,triad,dot once each", "bytes_per_step": step_bytes},
         "frac_of_hbm_peak": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "kernels": kernels,

@@ -10,7 +10,7 @@
  *              and hold n elements of the type named by `dtype`.
  *   Alignment  An array pointer only has to be a multiple of its element size
  *              (8 for OPAL_F64, 4 for OPAL_F32); anything else is
- *              OPAL_ERR_ALIGN.  Arrays that are 128-byte aligned, or that all
+ *              OPAL_ERR_ALIGN.  Arrays that are 1 KiB aligned, or that all
  *              share one misalignment, run on the fastest path.
  *   Aliasing   An output array must not overlap an input array of the same
  *              call (not checked; the result would be undefined).

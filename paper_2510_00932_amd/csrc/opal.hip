@@ -35,7 +35,7 @@ constexpr int kDotUnroll = 4;
 constexpr unsigned kDotGroupsPerCU = 1;
 constexpr unsigned kDotMaxGroups = 8192;   // 64 KiB of fp64 partials at most
 constexpr unsigned kFinalBlock = 256;
-constexpr unsigned kBodyAlign = 128;       // the vector body starts on a 128-byte line
+constexpr unsigned kBodyAlign = 1024;      // the vector body starts on a 1 KiB boundary
 constexpr size_t kMaxGrid = 0x7fffffffu;
 
 constexpr int kMaxDevices = 64;
