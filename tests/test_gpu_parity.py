@@ -259,3 +259,72 @@ def test_graph_replay_matches_oracle(parity, harness):
         assert (ec.download() == 5.0).all()
         res.fill_(float("nan"))
         torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ special values
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_special_values(harness, dtype):
+    """Signed zeros, subnormals, infinities, overflow and NaNs go through scale / add / triad exactly as
+    on the CPU.  Results that are numbers must match bit for bit (so subnormals are not flushed and
+    -0.0 stays -0.0); where the CPU result is a NaN the GPU result must be a NaN too (which NaN is
+    produced by inf - inf or 0 * inf differs between the two instruction sets and is not compared)."""
+    import oracle
+    info = np.finfo(dtype)
+    tiny, big = info.tiny, info.max
+    sub = dtype(tiny) / dtype(8)                      # a subnormal
+    specials = np.array([0.0, -0.0, sub, -sub, tiny, -tiny, 1.0, -1.0, big, -big, np.inf, -np.inf, np.nan,
+                         1.5, 3.0 * float(sub), 0.75], dtype=dtype)
+    # all ordered pairs (x, y) and, for the third operand, a rotation of the same list
+    x = np.repeat(specials, specials.size)
+    y = np.tile(specials, specials.size)
+    z = np.roll(y, 5)
+    pad = (-x.size) % 1024 + 1024 + 3                 # a few whole tiles and a ragged tail
+    x, y, z = (np.concatenate([v, np.full(pad, 0.25, dtype)]) for v in (x, y, z))
+    bits = np.uint64 if dtype == np.float64 else np.uint32
+
+    def compare(got, want, what):
+        nan_w, nan_g = np.isnan(want), np.isnan(got)
+        assert np.array_equal(nan_w, nan_g), "%s: NaN positions differ" % what
+        ok = nan_w | (got.view(bits) == want.view(bits))
+        bad = np.nonzero(~ok)[0]
+        assert bad.size == 0, "%s: %d differ, first i=%d gpu %r cpu %r" % (what, bad.size, bad[0], got[bad[0]], want[bad[0]])
+
+    impl = harness.GpuImpl((0, 1, 0))
+    for s in (0.4, -0.75, 0.0, float(big), 2.0):
+        with np.errstate(all="ignore"):
+            hb, gb = np.zeros_like(x), np.zeros_like(x)
+            oracle.scale(hb, x.copy(), s)
+            impl.scale(gb, x.copy(), s)
+            compare(gb, hb, "scale by %r" % s)
+            hc, gc = np.zeros_like(x), np.zeros_like(x)
+            oracle.add(x.copy(), y.copy(), hc)
+            impl.add(x.copy(), y.copy(), gc)
+            compare(gc, hc, "add")
+            ha, ga = np.zeros_like(x), np.zeros_like(x)
+            oracle.triad(ha, y.copy(), z.copy(), s)
+            impl.triad(ga, y.copy(), z.copy(), s)
+            compare(ga, ha, "triad with s = %r" % s)
+    # copy moves every bit pattern, NaN payloads included
+    weird = np.arange(x.size, dtype=bits) * bits(0x9E3779B97F4A7C15 if dtype == np.float64 else 0x9E3779B9)
+    src = weird.view(dtype)
+    dst = np.zeros_like(src)
+    impl.copy(src.copy(), dst)
+    assert np.array_equal(dst.view(bits), weird)
+
+
+def test_random_lengths_offsets_and_scalars(parity):
+    """Seeded random cases: length, per-array misalignment, element type, value range and scalar."""
+    rng = np.random.RandomState(20251)
+    for case in range(80):
+        dtype = DTYPES[rng.randint(2)]
+        n = int(rng.randint(0, 1 << int(rng.randint(4, 19))))
+        offsets = tuple(int(v) for v in rng.randint(0, 9, size=3))
+        lo, hi = ((0.5, 1.5), (-1.0, 1.0), (-1e3, 1e3))[rng.randint(3)]
+        s = float(rng.choice([0.4, -0.75, 1.0, -1.0, 3.0, 1e-3, float(rng.uniform(-2, 2))]))
+        arrays = [oi.uniform_array(1000 + case, k, n, dtype, lo, hi) for k in range(3)]
+        try:
+            parity.run_chain(arrays, s, offsets)
+        except AssertionError as e:
+            raise AssertionError("case %d (dtype=%s n=%d offsets=%s range=(%g,%g) s=%r): %s"
+                                 % (case, np.dtype(dtype).name, n, offsets, lo, hi, s, e))
