@@ -17,6 +17,19 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-ffp-contract=off",
          "-fPIC", "-shared", "-Wall", "-Wextra", "-Wno-unused-command-line-argument"]
 
 
+STUDY_SRC = os.path.join(HERE, "csrc", "shape_study.hip")
+STUDY_BIN = os.path.join(HERE, "shape_study")
+
+
+def build_shape_study() -> str:
+    """The stand-alone program that runs the alternative launch shapes side by side (for rocprofv3)."""
+    flags = [f for f in FLAGS if f not in ("-fPIC", "-shared")]
+    tmp = STUDY_BIN + ".tmp.%d" % os.getpid()
+    subprocess.run([HIPCC, *flags, STUDY_SRC, "-o", tmp], check=True)
+    os.replace(tmp, STUDY_BIN)
+    return STUDY_BIN
+
+
 def is_stale() -> bool:
     return (not os.path.exists(LIB)) or any(os.path.getmtime(d) > os.path.getmtime(LIB) for d in DEPS)
 
@@ -32,3 +45,4 @@ def build(force: bool = True) -> str:
 
 if __name__ == "__main__":
     print(build(force=True))
+    print(build_shape_study())
