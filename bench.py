@@ -36,7 +36,7 @@ KERNELS = ("copy", "scale", "add", "triad", "dot")
 
 def kernel_source_digest():
     h = hashlib.sha256()
-    for rel in ("paper_2510_00932_amd/csrc/stream_kernels.hpp", "paper_2510_00932_amd/csrc/opal.hip"):
+    for rel in ("paper_2510_00932_amd/csrc/stream_kernels.hpp", "paper_2510_00932_amd/csrc/launch_shapes.hpp"):
         with open(os.path.join(ROOT, rel), "rb") as f:
             h.update(f.read())
     return h.hexdigest()[:16]

@@ -6,37 +6,16 @@
 //   hipcc --offload-arch=gfx950 -O3 -ffp-contract=off \
 //         -Xclang -target-feature -Xclang -packed-fp32-ops -shared -fPIC
 
+#include <atomic>
+
 #include "../../include/opal.h"
+#include "launch_shapes.hpp"
 #include "lds_kernel.hpp"
 #include "stream_kernels.hpp"
 
 namespace {
 
 using namespace opal;
-
-// Launch shapes (chosen by measurement on MI355X at n = 2^28 fp64).
-// Elementwise: wavefront-sized workgroups, one 16-byte vector per lane, as many
-// workgroups as the body has 1 KiB runs; loads and stores non-temporal.
-// Dot: one workgroup of kDotBlock threads per compute unit, each looping over
-// tiles of kDotBlock * kDotUnroll vectors.
-//
-// Arrays of at most kCacheResidentBytes each (three of them fit the 256 MB
-// Infinity Cache together) are expected to be touched again by the next call:
-// they get temporal accesses, 256-lane workgroups (wave-sized ones would make
-// the dispatcher the bottleneck at these sizes) and 512-thread dot workgroups.
-// Measured crossover on MI355X, chain of the five kernels back to back: temporal
-// wins by 5-8 % up to 92 MiB per array and loses by 10 % from 128 MiB on.
-constexpr size_t kCacheResidentBytes = (size_t)96 << 20;
-constexpr int kStreamBlock = kWave;
-constexpr int kResidentBlock = 256;
-constexpr unsigned kDotBlock = 256;
-constexpr unsigned kDotResidentBlock = 512;
-constexpr int kDotUnroll = 4;
-constexpr unsigned kDotGroupsPerCU = 1;
-constexpr unsigned kDotMaxGroups = 8192;   // 64 KiB of fp64 partials at most
-constexpr unsigned kFinalBlock = 256;
-constexpr unsigned kBodyAlign = 1024;      // the vector body starts on a 1 KiB boundary
-constexpr size_t kMaxGrid = 0x7fffffffu;
 
 constexpr int kMaxDevices = 64;
 
@@ -61,14 +40,18 @@ bool launch(void (*kernel)(Params...), unsigned grid, unsigned block, hipStream_
 
 // Compute units of the current device (cached per device id); 0 on failure.
 unsigned compute_units() {
-  static int cached[kMaxDevices];
+  static std::atomic<int> cached[kMaxDevices];   // zero-initialised; any thread may fill an entry
   int dev = 0;
   if (!hip_ok(hipGetDevice(&dev))) return 0;
-  if (dev >= 0 && dev < kMaxDevices && cached[dev] > 0) return (unsigned)cached[dev];
+  const bool slot = dev >= 0 && dev < kMaxDevices;
+  if (slot) {
+    const int known = cached[dev].load(std::memory_order_relaxed);
+    if (known > 0) return (unsigned)known;
+  }
   int cus = 0;
   if (!hip_ok(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) || cus <= 0)
     return 0;
-  if (dev >= 0 && dev < kMaxDevices) cached[dev] = cus;
+  if (slot) cached[dev].store(cus, std::memory_order_relaxed);
   return (unsigned)cus;
 }
 

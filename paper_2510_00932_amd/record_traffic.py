@@ -28,7 +28,7 @@ KERNEL_KEYS = (("copy", "(opal::Op)0"), ("scale", "(opal::Op)1"), ("add", "(opal
 
 def source_digest():
     h = hashlib.sha256()
-    for rel in ("paper_2510_00932_amd/csrc/stream_kernels.hpp", "paper_2510_00932_amd/csrc/opal.hip"):
+    for rel in ("paper_2510_00932_amd/csrc/stream_kernels.hpp", "paper_2510_00932_amd/csrc/launch_shapes.hpp"):
         with open(os.path.join(ROOT, rel), "rb") as f:
             h.update(f.read())
     return h.hexdigest()[:16]

@@ -328,3 +328,11 @@ def test_random_lengths_offsets_and_scalars(parity):
         except AssertionError as e:
             raise AssertionError("case %d (dtype=%s n=%d offsets=%s range=(%g,%g) s=%r): %s"
                                  % (case, np.dtype(dtype).name, n, offsets, lo, hi, s, e))
+
+
+def test_array_larger_than_4_gib(parity):
+    """2^29 + 4099 fp64 elements per array: byte offsets no longer fit 32 bits."""
+    w = oi.workload(4)
+    n = (1 << 29) + 4099
+    arrays = [oi.uniform_array(w.seed, k, n, np.float64, w.lo, w.hi, threads=16) for k in range(3)]
+    parity.run_chain(arrays, w.s, (1, 1, 1), check_all_arrays_each_step=False)
