@@ -1,5 +1,5 @@
 /* libopal: the five bandwidth-bound streaming vector kernels that the paper uses
- * as its "simple", memory-bound optimisation subjects (Table 1: Copy, Mul, Add,
+ * as its small, memory-bound optimisation subjects (Table 1: Copy, Mul, Add,
  * Triad, Dot; Section 5.2), as hand-written HIP kernels for one MI355X
  * (CDNA4, gfx950) behind a C ABI.
  *
@@ -89,9 +89,9 @@ int opal_dot(const void* a, const void* b, size_t n, int dtype,
              void* workspace, size_t workspace_bytes, double* result, void* stream);
 
 /* LDS streaming microkernel: the analogue, for this chip's 160 KiB local data share, of the
- * shared-memory benchmark the paper lists beside the five kernels (Table 1: "Shmembench",
- * parameter rep = kernel repetition count, 300..1500, default 600; Section 5.2: "shared-memory
- * operations").  The paper gives no definition, so this one is the library's own:
+ * shared-memory benchmark the paper lists beside the five kernels (Table 1: the Shmembench row,
+ * parameter rep = kernel repetition count, 300..1500, default 600; Section 5.2 says it exercises
+ * shared memory).  The paper gives no definition, so this one is the library's own:
  *
  *   The arrays are cut into tiles of OPAL_LDS_TILE_VECTORS (1024) 16-byte vectors (2048 fp64
  *   or 4096 fp32 elements).  A tile is loaded into the LDS and then goes through `rep` rounds;
