@@ -28,7 +28,16 @@
  *              thrown.  Argument errors are found on the host before any GPU
  *              work is enqueued, and then nothing is enqueued.  n == 0 is
  *              valid: nothing is launched (opal_dot still stores 0.0).
- *   Sizes      n is a size_t element count; arrays larger than 2 GiB are fine.
+ *   Sizes      n is a size_t element count; arrays larger than 2 GiB are fine.  A
+ *              dispatch holds at most 2^31 work-items, so a very large elementwise
+ *              call is issued as several launches (one per 32 GiB of an array with
+ *              fp64 or fp32 elements) on the same stream; only an n whose byte count
+ *              does not fit half the address space is refused (OPAL_ERR_SIZE).
+ *   Runtime    The library links the HIP runtime it finds at load time.  A process
+ *              must use ONE copy of that runtime: streams and device pointers made
+ *              by another copy (for instance the one a Python package ships, when
+ *              the library was bound to the system's) are foreign to it.  Load the
+ *              library after the module that owns the streams and pointers.
  */
 #ifndef OPAL_H
 #define OPAL_H
@@ -47,7 +56,8 @@ enum {
   OPAL_ERR_ALIGN = 3,     /* a pointer is not a multiple of its element size (workspace/result: 8) */
   OPAL_ERR_WORKSPACE = 4, /* workspace_bytes < opal_dot_workspace_bytes(n, dtype) */
   OPAL_ERR_LAUNCH = 5,    /* the HIP runtime refused a query or a kernel launch */
-  OPAL_ERR_SIZE = 6       /* n needs more than 2^31 - 1 workgroups, or is not a whole number of LDS tiles */
+  OPAL_ERR_SIZE = 6       /* n * element size does not fit an address, an LDS call's n is not a whole number
+                             of tiles, or a tuning value is out of range */
 };
 
 /* Element types (passed as int). */
@@ -80,13 +90,41 @@ size_t opal_dot_workspace_bytes(size_t n, int dtype);
  * fp64 (also for OPAL_F32), 8-byte aligned, written.
  * Two kernels on `stream`: each workgroup of the first writes one fp64 partial
  * sum to the workspace, the second adds the partials in a fixed order.  No
- * atomics: for given (pointers' alignment, n, dtype, device) the result is
- * bit-reproducible from run to run.  OPAL_F64 accumulates in fp64 throughout
+ * atomics: for given (pointers' alignment, n, dtype, device, pacing setting) the
+ * result is bit-reproducible from run to run.  OPAL_F64 accumulates in fp64 throughout
  * (with fused multiply-adds); OPAL_F32 accumulates in fp32 within a thread and
  * a wavefront and in fp64 from there on.
- * Calls that share a workspace must be ordered (same stream, or synchronised). */
+ * Calls that share a workspace must be ordered (same stream, or synchronised).
+ * n == 0 stores 0.0; result and workspace must still be valid pointers (a NULL
+ * workspace is OPAL_ERR_NULL also for n == 0: the check does not depend on n). */
 int opal_dot(const void* a, const void* b, size_t n, int dtype,
              void* workspace, size_t workspace_bytes, double* result, void* stream);
+
+/* Launch shapes for arrays far beyond the caches ("paced" shapes).  For arrays of at least
+ * 192 MiB on an MI355X the five kernels run as persistent wavefronts that issue their loads and
+ * stores in bursts on a common timetable read off the chip-wide constant-rate counter, so that
+ * HBM sees one stream and one direction at a time (about 2 % more bytes per second for the
+ * elementwise kernels, 4 % for Dot, than workgroups handed out in index order).  Results are the
+ * same bits either way.  The timetable keeps a few device words of feedback inside the library's
+ * device image (one copy per GPU); calls that overlap on one GPU share them, which can only cost
+ * speed.  opal_set_pacing(0) switches to index-ordered workgroups for every size (the
+ * environment variable OPAL_PACING=0 does the same before the first call); opal_get_pacing()
+ * returns the current setting.  Process-wide, not per stream. */
+void opal_set_pacing(int enabled);
+int opal_get_pacing(void);
+
+/* Tuning hook for the timetable of one kind of paced kernel (0: Copy and Mul, 1: Add and Triad,
+ * 2: Dot): the rate the timetable asks of memory in TB/s (1 TB = 1e12 B), where in the period the
+ * store burst goes (fraction in [0,1); 0 = as soon as the data has arrived), for Dot how long
+ * after the burst of `a` the burst of `b` goes (fraction of the period; for Add and Triad the
+ * same for their second input), how far apart the accesses of one burst are spread (fraction of
+ * the period, below 0.25; 0 = all at once), how many ticks late a
+ * wavefront has to be before the timetable is pushed back, whether lateness is fed back at
+ * all, and which bit of the workgroup index splits the wavefronts into the two sets (0..8; 3 puts
+ * whole compute units into one set).  Defaults are the measured optimum on MI355X; a timetable that asks too much degrades to
+ * unordered traffic, it never affects results.  OPAL_ERR_SIZE for a value out of range. */
+int opal_pacing_configure(int kind, double terabytes_per_second, double store_at, double second_input_at,
+                          double gap, unsigned tolerance_ticks, int feedback, unsigned set_bit);
 
 /* LDS streaming microkernel: the analogue, for this chip's 160 KiB local data share, of the
  * shared-memory benchmark the paper lists beside the five kernels (Table 1: the Shmembench row,

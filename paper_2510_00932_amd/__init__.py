@@ -20,6 +20,9 @@ from .binding import (  # noqa: F401
     opal_copy,
     opal_dot,
     opal_dot_workspace_bytes,
+    opal_get_pacing,
+    opal_pacing_configure,
+    opal_set_pacing,
     opal_lds_stream,
     opal_lds_tile_elements,
     opal_scale,

@@ -56,6 +56,12 @@ def load():
     lib.opal_dot.argtypes = [vp, vp, sz, it, vp, sz, vp, vp]
     for name in ("opal_copy", "opal_scale", "opal_add", "opal_triad", "opal_dot"):
         getattr(lib, name).restype = it
+    lib.opal_set_pacing.argtypes = [it]
+    lib.opal_set_pacing.restype = None
+    lib.opal_get_pacing.argtypes = []
+    lib.opal_get_pacing.restype = it
+    lib.opal_pacing_configure.argtypes = [it, dbl, dbl, dbl, dbl, ctypes.c_uint, it, ctypes.c_uint]
+    lib.opal_pacing_configure.restype = it
     lib.opal_dot_workspace_bytes.argtypes = [sz, it]
     lib.opal_dot_workspace_bytes.restype = sz
     lib.opal_status_string.argtypes = [it]
@@ -151,6 +157,21 @@ def opal_dot(a, b, n, dtype, workspace, workspace_bytes, result, stream=None):
     """result[0] = sum a[i]*b[i] (result: one fp64 in device memory)."""
     _check(load().opal_dot(_ptr(a), _ptr(b), n, _dtype_of(a, dtype), _ptr(workspace), workspace_bytes,
                            _ptr(result), _stream(stream)))
+
+
+def opal_set_pacing(enabled) -> None:
+    load().opal_set_pacing(1 if enabled else 0)
+
+
+def opal_get_pacing() -> bool:
+    return bool(load().opal_get_pacing())
+
+
+def opal_pacing_configure(kind, terabytes_per_second, store_at, second_input_at, gap, tolerance_ticks, feedback,
+                          set_bit=3):
+    _check(load().opal_pacing_configure(int(kind), float(terabytes_per_second), float(store_at),
+                                        float(second_input_at), float(gap), int(tolerance_ticks), 1 if feedback else 0,
+                                        int(set_bit)))
 
 
 def opal_lds_tile_elements(dtype) -> int:

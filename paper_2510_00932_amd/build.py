@@ -4,8 +4,9 @@ import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 SRC = os.path.join(HERE, "csrc", "opal.hip")
-DEPS = [SRC, os.path.join(HERE, "csrc", "stream_kernels.hpp"), os.path.join(HERE, "csrc", "lds_kernel.hpp"), os.path.join(HERE, "csrc", "launch_shapes.hpp"),
-        os.path.join(os.path.dirname(HERE), "include", "opal.h")]
+DEPS = [SRC] + [os.path.join(HERE, "csrc", f) for f in
+                ("stream_kernels.hpp", "lds_kernel.hpp", "launch_shapes.hpp", "launch_plan.hpp", "pacing.hpp")] + \
+    [os.path.join(os.path.dirname(HERE), "include", "opal.h")]
 LIB = os.path.join(HERE, "libopal.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

@@ -1,0 +1,178 @@
+// Work decomposition of the streaming kernels, as plain arithmetic with no GPU dependency: which
+// element of an array is moved by which workgroup, wavefront and lane, for every launch shape the
+// library uses.  The host code plans launches with these functions and the kernels index with
+// them, so a host-only program can check, element by element, that every shape covers every
+// element exactly once (tests/host_checks/partition_check.cpp does, also under sanitizers).
+//
+// Vocabulary
+//   vector : 16 bytes (2 fp64 or 4 fp32 elements), the unit one lane moves per access
+//   run    : 64 consecutive vectors = 1 KiB, what one wavefront moves per access
+//   head   : scalar elements before the vector body (up to the first 1 KiB boundary of the
+//            array that steers the split: the output; for dot, `a`)
+//   body   : nvec vectors;  tail : the < one-vector rest
+#pragma once
+
+#include <stddef.h>
+#include <stdint.h>
+
+#if defined(__HIPCC__)
+#define OPAL_HD __host__ __device__ inline
+#else
+#define OPAL_HD inline
+#endif
+
+namespace opal {
+namespace plan {
+
+constexpr unsigned kRunVectors = 64;        // one wavefront, one vector per lane
+constexpr unsigned kBodyAlignBytes = 1024;  // the vector body starts on a 1 KiB boundary
+
+struct Split {
+  unsigned head;   // scalar elements before the body
+  size_t nvec;     // vectors in the body
+  unsigned tail;   // scalar elements after the body
+};
+
+// elem = element size in bytes (8 or 4); addr = address of element 0 of the steering array.
+OPAL_HD Split split(uintptr_t addr, size_t n, unsigned elem) {
+  const unsigned lanes = 16u / elem;
+  size_t head = ((kBodyAlignBytes - (addr % kBodyAlignBytes)) % kBodyAlignBytes) / elem;
+  if (head > n) head = n;
+  const size_t nvec = (n - head) / lanes;
+  return Split{(unsigned)head, nvec, (unsigned)(n - head - nvec * lanes)};
+}
+
+// Index of the i-th of the head + tail scalar elements (0 <= i < head + tail).
+OPAL_HD size_t edge_element(const Split& s, unsigned lanes, unsigned i) {
+  return i < s.head ? (size_t)i : (size_t)s.head + s.nvec * lanes + (i - s.head);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Dispatcher-ordered elementwise shape: workgroup g of `block` lanes moves vectors
+// g*block .. g*block + block - 1; the last workgroup also moves the head and tail scalars.
+// One dispatch holds at most kMaxWorkItems work-items (a dispatch's global size is a 32-bit
+// count), so a large body is cut into segments, each a launch of its own on element-shifted
+// pointers.  Segment 0 carries the head, the last segment the tail.
+
+constexpr size_t kMaxWorkItems = (size_t)1 << 31;
+
+OPAL_HD size_t stream_vector(unsigned block, unsigned group, unsigned lane) { return (size_t)group * block + lane; }
+
+struct Segment {
+  size_t elem_offset;   // added to every array pointer
+  unsigned head;        // as seen by this launch
+  size_t nvec;
+  size_t n;             // elements this launch covers (head + nvec*lanes + tail)
+  unsigned groups;      // workgroups (>= 1)
+};
+
+// max_items: work-items one launch may hold (smaller values only in tests, to replay the
+// multi-launch path on small arrays).
+OPAL_HD size_t segment_vectors(unsigned block, size_t max_items = kMaxWorkItems) {
+  return (max_items / block) * block;
+}
+
+OPAL_HD size_t segment_count(const Split& s, unsigned block, size_t max_items = kMaxWorkItems) {
+  const size_t per = segment_vectors(block, max_items);
+  const size_t c = (s.nvec + per - 1) / per;
+  return c < 1 ? 1 : c;
+}
+
+OPAL_HD Segment segment(const Split& s, unsigned lanes, unsigned block, size_t index,
+                        size_t max_items = kMaxWorkItems) {
+  const size_t per = segment_vectors(block, max_items);
+  const size_t count = segment_count(s, block, max_items);
+  const size_t v0 = index * per;
+  size_t nv = s.nvec > v0 ? s.nvec - v0 : 0;
+  if (nv > per) nv = per;
+  Segment g;
+  g.elem_offset = index == 0 ? 0 : (size_t)s.head + v0 * lanes;
+  g.head = index == 0 ? s.head : 0u;
+  g.nvec = nv;
+  g.n = (size_t)g.head + nv * lanes + (index + 1 == count ? s.tail : 0u);
+  const size_t groups = (nv + block - 1) / block;
+  g.groups = (unsigned)(groups < 1 ? 1 : groups);
+  return g;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Paced shape (elementwise and dot): `waves` persistent wavefronts, one per workgroup, in two
+// sets.  The full runs of the body are cut into chunks of (waves/2) * K runs; set s takes the
+// chunks of parity s, wavefront j of a set moves runs  chunk*chunk_runs + j + k*(waves/2),
+// k < K, of each of its chunks.  What is left (fewer runs than one chunk, a ragged last run,
+// head and tail scalars) is moved afterwards by all wavefronts together, wavefront w taking
+// runs  rest_run0 + w + m*waves.  The last wavefront also moves the head and tail scalars.
+
+struct Paced {
+  Split split;
+  unsigned waves;       // a multiple of 2 << set_bit
+  unsigned set_bit;     // see paced_set
+  unsigned k;           // runs per wavefront per chunk
+  size_t chunk_runs;    // (waves / 2) * k
+  size_t nchunks;
+  size_t rest_run0;     // first run of the rest
+  size_t total_runs;    // ceil(nvec / 64): the last one may be ragged
+};
+
+OPAL_HD Paced paced(const Split& s, unsigned waves, unsigned k, unsigned set_bit) {
+  Paced p;
+  p.split = s;
+  p.waves = waves;
+  p.set_bit = set_bit;
+  p.k = k;
+  p.chunk_runs = (size_t)(waves / 2) * k;
+  const size_t full_runs = s.nvec / kRunVectors;
+  p.nchunks = full_runs / p.chunk_runs;
+  p.rest_run0 = p.nchunks * p.chunk_runs;
+  p.total_runs = (s.nvec + kRunVectors - 1) / kRunVectors;
+  return p;
+}
+
+// Workgroup index -> (set, index within the set): bit `set_bit` of the workgroup index is the
+// set, the remaining bits, closed up, are the index.  The hardware deals workgroups to the eight
+// XCDs round-robin and, inside an XCD, to its 32 compute units round-robin, so workgroup g runs
+// on compute unit (g / 8) mod 32 of XCD g mod 8, and the choice of the bit decides where the two
+// sets live: bit 3 puts whole compute units into one set (every wavefront of a compute unit
+// then loads at the same time and stores at the same time: its memory path sees a pure load
+// burst, then a pure store burst), bit 8 gives every compute unit half of each set, bits 0-2
+// split by XCD.  Bits below set_bit stay in the index, so consecutive runs of a chunk still go
+// to different XCDs.  `waves` must be a multiple of 2 << set_bit.
+OPAL_HD unsigned paced_set(unsigned group, unsigned set_bit) { return (group >> set_bit) & 1u; }
+OPAL_HD unsigned paced_index(unsigned group, unsigned set_bit) {
+  return ((group >> (set_bit + 1)) << set_bit) | (group & ((1u << set_bit) - 1u));
+}
+
+OPAL_HD size_t paced_run(const Paced& p, size_t chunk, unsigned index, unsigned k) {
+  return chunk * p.chunk_runs + index + (size_t)k * (p.waves / 2);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Tiled dot shape (arrays that fit the caches): `groups` workgroups of `block` threads loop
+// over tiles of block * unroll vectors, workgroup g taking tiles g, g + groups, ...; the
+// workgroup whose turn comes after the last full tile also takes the ragged rest and the head
+// and tail scalars.
+
+struct Tiled {
+  Split split;
+  unsigned block, unroll, groups;
+  size_t tile_vectors;
+  size_t full_tiles;
+};
+
+OPAL_HD Tiled tiled(const Split& s, unsigned block, unsigned unroll, unsigned max_groups) {
+  Tiled t;
+  t.split = s;
+  t.block = block;
+  t.unroll = unroll;
+  t.tile_vectors = (size_t)block * unroll;
+  t.full_tiles = s.nvec / t.tile_vectors;
+  size_t g = t.full_tiles < 1 ? 1 : t.full_tiles;
+  if (g > max_groups) g = max_groups;
+  t.groups = (unsigned)g;
+  return t;
+}
+
+OPAL_HD unsigned tiled_ragged_group(const Tiled& t) { return (unsigned)(t.full_tiles % t.groups); }
+
+}  // namespace plan
+}  // namespace opal

@@ -1,5 +1,5 @@
-// Launch shapes of the streaming kernels: everything that, together with
-// stream_kernels.hpp, decides what the GPU executes for a given call.  Kept in a
+// Launch shapes of the streaming kernels: everything that, together with stream_kernels.hpp,
+// pacing.hpp and launch_plan.hpp, decides what the GPU executes for a given call.  Kept in a
 // file of its own so that measured figures can be tied to exactly these choices.
 #pragma once
 
@@ -9,19 +9,21 @@
 
 namespace opal {
 
-// Launch shapes (chosen by measurement on MI355X at n = 2^28 fp64).
-// Elementwise: wavefront-sized workgroups, one 16-byte vector per lane, as many
-// workgroups as the body has 1 KiB runs; loads and stores non-temporal.
-// Dot: one workgroup of kDotBlock threads per compute unit, each looping over
-// tiles of kDotBlock * kDotUnroll vectors.
+// Three regimes, by the size of one array (chosen by measurement on MI355X):
 //
-// Arrays of at most kCacheResidentBytes each (three of them fit the 256 MB
-// Infinity Cache together) are expected to be touched again by the next call:
-// they get temporal accesses, 256-lane workgroups (wave-sized ones would make
-// the dispatcher the bottleneck at these sizes) and 512-thread dot workgroups.
-// Measured crossover on MI355X, chain of the five kernels back to back: temporal
-// wins by 5-8 % up to 92 MiB per array and loses by 10 % from 128 MiB on.
+//   up to kCacheResidentBytes  (three such arrays fit the 256 MB Infinity Cache together, so the
+//       next call is expected to find them there): temporal accesses, 256-lane workgroups in
+//       dispatcher order (wave-sized ones would make the dispatcher the bottleneck at these
+//       sizes), tiled dot with 512-thread workgroups.  Measured crossover, chain of the five
+//       kernels back to back: temporal wins by 5-8 % up to 92 MiB per array and loses by 10 %
+//       from 128 MiB on.
+//   up to kPacedMinBytes: non-temporal accesses, wave-sized workgroups in dispatcher order, one
+//       16-byte vector per lane; tiled dot, one 256-thread workgroup per compute unit.
+//   above: the paced shapes (persistent wavefronts on a clock timetable), when the device is
+//       the one the timetable was measured on; otherwise as the middle regime.
 constexpr size_t kCacheResidentBytes = (size_t)96 << 20;
+constexpr size_t kPacedMinBytes = (size_t)192 << 20;
+
 constexpr int kStreamBlock = kWave;
 constexpr int kResidentBlock = 256;
 constexpr unsigned kDotBlock = 256;
@@ -30,7 +32,28 @@ constexpr int kDotUnroll = 4;
 constexpr unsigned kDotGroupsPerCU = 1;
 constexpr unsigned kDotMaxGroups = 8192;   // 64 KiB of fp64 partials at most
 constexpr unsigned kFinalBlock = 256;
-constexpr unsigned kBodyAlign = 1024;      // the vector body starts on a 1 KiB boundary
-constexpr size_t kMaxGrid = 0x7fffffffu;
+
+// Paced shapes.  Rates are what the timetable asks of the memory system, in bytes per
+// microsecond (= MB/s / 1e... i.e. 7.0e6 is 7.0 TB/s): slightly more than HBM sustains, so the
+// timetable, not the queues, orders the traffic, and the feedback of pacing.hpp absorbs the
+// difference.  Measured optimum on MI355X (8 TB/s HBM3E, 256 compute units, 100 MHz counter).
+struct PacedShape {
+  unsigned waves;          // persistent wavefronts (8 or 4 per compute unit)
+  unsigned k;              // 1 KiB runs per wavefront per burst
+  unsigned set_bit;        // bit of the workgroup index that selects the set (plan::paced_set)
+  double bytes_per_us;     // timetable rate
+  double store_at;         // store burst at this fraction of the period (0: as soon as data is there)
+  double second_input_at;  // burst of the second input at this fraction of the period after the first
+  double gap;              // accesses of a burst this fraction of the period apart (0: all at once)
+  unsigned tolerance;      // ticks of lateness before reporters push the timetable back
+  bool feedback;
+};
+constexpr unsigned kPacedCUs = 256;             // the timetable is for this chip only
+constexpr int kPacedK1 = 8;                     // one-input kernels (copy, scale): K
+constexpr int kPacedK2 = 4;                     // two-input kernels (add, triad): K
+constexpr int kPacedKDot = 8;
+constexpr PacedShape kPacedOneInput = {2048, kPacedK1, 3, 7.05e6, 0.75, 0.0, 0.02, 400, true};
+constexpr PacedShape kPacedTwoInputs = {2048, kPacedK2, 3, 7.10e6, 0.0, 0.0, 0.03, 400, true};
+constexpr PacedShape kPacedDot = {1024, kPacedKDot, 3, 7.60e6, 0.0, 0.25, 0.0, 0, false};
 
 }  // namespace opal

@@ -7,8 +7,11 @@
 //         -Xclang -target-feature -Xclang -packed-fp32-ops -shared -fPIC
 
 #include <atomic>
+#include <cstdlib>
+#include <cstring>
 
 #include "../../include/opal.h"
+#include "launch_plan.hpp"
 #include "launch_shapes.hpp"
 #include "lds_kernel.hpp"
 #include "stream_kernels.hpp"
@@ -38,46 +41,90 @@ bool launch(void (*kernel)(Params...), unsigned grid, unsigned block, hipStream_
   return hip_ok(pack(args...));
 }
 
-// Compute units of the current device (cached per device id); 0 on failure.
-unsigned compute_units() {
-  static std::atomic<int> cached[kMaxDevices];   // zero-initialised; any thread may fill an entry
-  int dev = 0;
-  if (!hip_ok(hipGetDevice(&dev))) return 0;
-  const bool slot = dev >= 0 && dev < kMaxDevices;
-  if (slot) {
-    const int known = cached[dev].load(std::memory_order_relaxed);
-    if (known > 0) return (unsigned)known;
-  }
-  int cus = 0;
-  if (!hip_ok(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) || cus <= 0)
-    return 0;
-  if (slot) cached[dev].store(cus, std::memory_order_relaxed);
-  return (unsigned)cus;
-}
+// Device words of the pacing feedback (pacing.hpp): a file-scope device array, one copy per GPU,
+// held until the process ends.  In host code the array's name is only a stand-in; its device
+// address comes from hipGetSymbolAddress, once per device.
+static __device__ __align__(256) unsigned long long pace_words[kFeedbackWords];
 
-struct Split {
-  unsigned head;   // scalar elements before the body
-  size_t nvec;     // 16-byte vectors in the body
+// What the library needs to know about a device, looked up on the first call made with that
+// device current and cached by device id.
+struct DeviceInfo {
+  unsigned cus = 0;                       // compute units
+  unsigned ticks_per_us = 0;              // rate of the constant counter the timetable runs on
+  bool paced = false;                     // the paced shapes were measured on this kind of device
+  unsigned long long* feedback = nullptr; // device address of pace_words
 };
 
-// Head = elements from `steer` up to its next kBodyAlign-byte boundary (or all n).
-template <typename T>
-Split split(const void* steer, size_t n) {
-  constexpr size_t L = 16 / sizeof(T);
-  const uintptr_t addr = reinterpret_cast<uintptr_t>(steer);
-  size_t head = ((kBodyAlign - (addr % kBodyAlign)) % kBodyAlign) / sizeof(T);
-  if (head > n) head = n;
-  return Split{(unsigned)head, (n - head) / L};
+const DeviceInfo* device_info() {
+  static DeviceInfo info[kMaxDevices];
+  static std::atomic<int> ready[kMaxDevices];   // zero-initialised; 1 once info[dev] is complete
+  static thread_local DeviceInfo overflow;      // device ids beyond the table: looked up per call
+  int dev = 0;
+  if (!hip_ok(hipGetDevice(&dev))) return nullptr;
+  const bool slot = dev >= 0 && dev < kMaxDevices;
+  if (slot && ready[dev].load(std::memory_order_acquire)) return &info[dev];
+  DeviceInfo d;
+  int cus = 0, khz = 0;
+  if (!hip_ok(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) || cus <= 0) return nullptr;
+  d.cus = (unsigned)cus;
+  if (hip_ok(hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev)) && khz >= 1000)
+    d.ticks_per_us = (unsigned)(khz / 1000);
+  hipDeviceProp_t prop;
+  const bool gfx950 = hip_ok(hipGetDeviceProperties(&prop, dev)) && std::strncmp(prop.gcnArchName, "gfx950", 6) == 0;
+  void* ptr = nullptr;
+  if (hip_ok(hipGetSymbolAddress(&ptr, HIP_SYMBOL(pace_words)))) d.feedback = static_cast<unsigned long long*>(ptr);
+  d.paced = gfx950 && d.cus == kPacedCUs && d.ticks_per_us > 0 && d.feedback != nullptr;
+  if (!slot) {
+    overflow = d;
+    return &overflow;
+  }
+  info[dev] = d;   // two threads may both get here: they write the same values
+  ready[dev].store(1, std::memory_order_release);
+  return &info[dev];
+}
+
+// Run-time copies of the paced shapes (opal_pacing_configure may change the rates) and the switch.
+PacedShape g_shapes[3] = {kPacedOneInput, kPacedTwoInputs, kPacedDot};
+std::atomic<int> g_pacing{-1};   // -1: not decided yet (environment), 0: off, 1: on
+
+bool pacing_enabled() {
+  int v = g_pacing.load(std::memory_order_relaxed);
+  if (v < 0) {
+    const char* env = std::getenv("OPAL_PACING");
+    v = (env != nullptr && env[0] == '0') ? 0 : 1;
+    g_pacing.store(v, std::memory_order_relaxed);
+  }
+  return v != 0;
+}
+
+// Timetable of a paced launch: `streams` arrays, each moved waves * k KiB per period.
+Pace make_pace(const PacedShape& sh, unsigned streams, const DeviceInfo& dev) {
+  const double bytes = (double)sh.waves * sh.k * 1024.0 * streams;
+  const double period = bytes / sh.bytes_per_us * dev.ticks_per_us;
+  Pace pace;
+  pace.period = period < 16.0 ? 16u : (uint32_t)(period + 0.5);
+  pace.second_input = (uint32_t)(sh.second_input_at * pace.period);
+  pace.store = (uint32_t)(sh.store_at * pace.period);
+  pace.gap = (uint32_t)(sh.gap * pace.period);
+  pace.tolerance = sh.tolerance;
+  pace.feedback = sh.feedback ? dev.feedback : nullptr;
+  return pace;
 }
 
 bool aligned16_after(const void* p, unsigned head, size_t elem) {
   return ((reinterpret_cast<uintptr_t>(p) + (uintptr_t)head * elem) & 15u) == 0;
 }
 
-size_t dot_full_tiles(size_t nvec, unsigned block) { return nvec / ((size_t)block * (size_t)kDotUnroll); }
-
 template <typename T>
 bool cache_resident(size_t n) { return n * sizeof(T) <= kCacheResidentBytes; }
+
+// The paced shapes apply to arrays well beyond the caches, on the device they were measured on.
+template <typename T>
+bool use_paced(size_t n, const DeviceInfo* dev, const PacedShape& sh) {
+  if (dev == nullptr || !dev->paced || !pacing_enabled()) return false;
+  if (n < kPacedMinBytes / sizeof(T)) return false;
+  return n / ((size_t)(sh.waves / 2) * sh.k * (1024 / sizeof(T))) >= 16;   // at least 16 chunks
+}
 
 int check_ptr(const void* p, size_t n, size_t elem) {
   if (n == 0) return OPAL_OK;
@@ -86,25 +133,58 @@ int check_ptr(const void* p, size_t n, size_t elem) {
   return OPAL_OK;
 }
 
+// n * sizeof(T) must be addressable; anything else cannot be a real array.
+template <typename T>
+bool size_ok(size_t n) { return n <= (~(size_t)0 >> 1) / sizeof(T); }
+
+// Dispatcher-ordered shape: one launch per segment of the body (plan::segment).
 template <typename T, Op OP, int BLOCK, bool NT>
 int launch_stream_shape(T* out, const T* in0, const T* in1, T s, size_t n, hipStream_t stream) {
-  const Split sp = split<T>(out, n);
+  constexpr unsigned L = 16 / sizeof(T);
+  const plan::Split sp = plan::split(reinterpret_cast<uintptr_t>(out), n, sizeof(T));
   const bool aligned = aligned16_after(in0, sp.head, sizeof(T)) &&
                        (!kTwoInputs<OP> || aligned16_after(in1, sp.head, sizeof(T)));
-  size_t groups = (sp.nvec + BLOCK - 1) / BLOCK;
-  if (groups < 1) groups = 1;
-  if (groups > kMaxGrid) return OPAL_ERR_SIZE;
-  const bool ok = aligned ? launch(stream_kernel<T, OP, BLOCK, true, NT>, (unsigned)groups, (unsigned)BLOCK, stream,
-                                   out, in0, in1, s, sp.head, sp.nvec, n)
-                          : launch(stream_kernel<T, OP, BLOCK, false, NT>, (unsigned)groups, (unsigned)BLOCK, stream,
-                                   out, in0, in1, s, sp.head, sp.nvec, n);
+  const size_t count = plan::segment_count(sp, BLOCK);
+  for (size_t i = 0; i < count; ++i) {
+    const plan::Segment g = plan::segment(sp, L, BLOCK, i);
+    T* o = out + g.elem_offset;
+    const T* x = in0 + g.elem_offset;
+    const T* y = kTwoInputs<OP> ? in1 + g.elem_offset : nullptr;
+    const bool ok = aligned ? launch(stream_kernel<T, OP, BLOCK, true, NT>, g.groups, (unsigned)BLOCK, stream,
+                                     o, x, y, s, g.head, g.nvec, g.n)
+                            : launch(stream_kernel<T, OP, BLOCK, false, NT>, g.groups, (unsigned)BLOCK, stream,
+                                     o, x, y, s, g.head, g.nvec, g.n);
+    if (!ok) return OPAL_ERR_LAUNCH;
+  }
+  return OPAL_OK;
+}
+
+template <typename T, Op OP>
+int launch_paced(T* out, const T* in0, const T* in1, T s, size_t n, const DeviceInfo& dev, const PacedShape& sh,
+                 hipStream_t stream) {
+  constexpr int K = kTwoInputs<OP> ? kPacedK2 : kPacedK1;
+  const plan::Split sp = plan::split(reinterpret_cast<uintptr_t>(out), n, sizeof(T));
+  const bool aligned = aligned16_after(in0, sp.head, sizeof(T)) &&
+                       (!kTwoInputs<OP> || aligned16_after(in1, sp.head, sizeof(T)));
+  const plan::Paced p = plan::paced(sp, sh.waves, K, sh.set_bit);
+  const Pace pace = make_pace(sh, kTwoInputs<OP> ? 3u : 2u, dev);
+  const bool ok = aligned ? launch(paced_stream_kernel<T, OP, K, true>, sh.waves, (unsigned)kWave, stream,
+                                   out, in0, in1, s, p, pace)
+                          : launch(paced_stream_kernel<T, OP, K, false>, sh.waves, (unsigned)kWave, stream,
+                                   out, in0, in1, s, p, pace);
   return ok ? OPAL_OK : OPAL_ERR_LAUNCH;
 }
 
 template <typename T, Op OP>
 int launch_stream(T* out, const T* in0, const T* in1, T s, size_t n, hipStream_t stream) {
-  return cache_resident<T>(n) ? launch_stream_shape<T, OP, kResidentBlock, false>(out, in0, in1, s, n, stream)
-                              : launch_stream_shape<T, OP, kStreamBlock, true>(out, in0, in1, s, n, stream);
+  if (!size_ok<T>(n)) return OPAL_ERR_SIZE;
+  if (cache_resident<T>(n)) return launch_stream_shape<T, OP, kResidentBlock, false>(out, in0, in1, s, n, stream);
+  const PacedShape sh = g_shapes[kTwoInputs<OP> ? 1 : 0];
+  if (n >= kPacedMinBytes / sizeof(T)) {
+    const DeviceInfo* dev = device_info();
+    if (use_paced<T>(n, dev, sh)) return launch_paced<T, OP>(out, in0, in1, s, n, *dev, sh, stream);
+  }
+  return launch_stream_shape<T, OP, kStreamBlock, true>(out, in0, in1, s, n, stream);
 }
 
 template <Op OP>
@@ -135,31 +215,46 @@ unsigned dot_groups_bound(size_t n, int dtype) {
 }
 
 template <typename T, bool NT>
-bool launch_dot_pass1(const T* a, const T* b, size_t n, double* partials, unsigned block, unsigned cus,
+bool launch_dot_tiled(const T* a, const T* b, size_t n, double* partials, unsigned block, unsigned cus,
                       unsigned* groups_out, hipStream_t stream) {
-  const Split sp = split<T>(a, n);
+  const plan::Split sp = plan::split(reinterpret_cast<uintptr_t>(a), n, sizeof(T));
   const bool aligned = aligned16_after(b, sp.head, sizeof(T));
-  const size_t tiles = dot_full_tiles(sp.nvec, block);
-  size_t g = tiles < 1 ? 1 : tiles;
-  const unsigned bound = dot_groups_bound(n, sizeof(T) == 8 ? OPAL_F64 : OPAL_F32);
-  if (g > (size_t)cus * kDotGroupsPerCU) g = (size_t)cus * kDotGroupsPerCU;
-  if (g > bound) g = bound;
-  *groups_out = (unsigned)g;
-  return aligned ? launch(dot_partial_kernel<T, kDotUnroll, true, NT>, (unsigned)g, block, stream, a, b, partials,
-                          sp.head, sp.nvec, tiles, n)
-                 : launch(dot_partial_kernel<T, kDotUnroll, false, NT>, (unsigned)g, block, stream, a, b, partials,
-                          sp.head, sp.nvec, tiles, n);
+  unsigned cap = dot_groups_bound(n, sizeof(T) == 8 ? OPAL_F64 : OPAL_F32);
+  if (cap > cus * kDotGroupsPerCU) cap = cus * kDotGroupsPerCU;
+  const plan::Tiled t = plan::tiled(sp, block, kDotUnroll, cap);
+  *groups_out = t.groups;
+  return aligned ? launch(dot_partial_kernel<T, kDotUnroll, true, NT>, t.groups, block, stream, a, b, partials, t)
+                 : launch(dot_partial_kernel<T, kDotUnroll, false, NT>, t.groups, block, stream, a, b, partials, t);
+}
+
+template <typename T>
+bool launch_dot_paced(const T* a, const T* b, size_t n, double* partials, const DeviceInfo& dev,
+                      const PacedShape& sh, hipStream_t stream) {
+  const plan::Split sp = plan::split(reinterpret_cast<uintptr_t>(a), n, sizeof(T));
+  const bool aligned = aligned16_after(b, sp.head, sizeof(T));
+  const plan::Paced p = plan::paced(sp, sh.waves, kPacedKDot, sh.set_bit);
+  const Pace pace = make_pace(sh, 2u, dev);
+  return aligned ? launch(paced_dot_kernel<T, kPacedKDot, true>, sh.waves, (unsigned)kWave, stream, a, b, partials, p, pace)
+                 : launch(paced_dot_kernel<T, kPacedKDot, false>, sh.waves, (unsigned)kWave, stream, a, b, partials, p, pace);
 }
 
 template <typename T>
 int launch_dot(const T* a, const T* b, size_t n, double* partials, double* result, hipStream_t stream) {
+  if (!size_ok<T>(n)) return OPAL_ERR_SIZE;
   unsigned groups = 0;
   if (n > 0) {
-    const unsigned cus = compute_units();
-    if (cus == 0) return OPAL_ERR_LAUNCH;
-    const bool ok = cache_resident<T>(n)
-                        ? launch_dot_pass1<T, false>(a, b, n, partials, kDotResidentBlock, cus, &groups, stream)
-                        : launch_dot_pass1<T, true>(a, b, n, partials, kDotBlock, cus, &groups, stream);
+    const DeviceInfo* dev = device_info();
+    if (dev == nullptr) return OPAL_ERR_LAUNCH;
+    const PacedShape sh = g_shapes[2];
+    bool ok;
+    if (use_paced<T>(n, dev, sh) && sh.waves <= dot_groups_bound(n, sizeof(T) == 8 ? OPAL_F64 : OPAL_F32)) {
+      groups = sh.waves;
+      ok = launch_dot_paced<T>(a, b, n, partials, *dev, sh, stream);
+    } else if (cache_resident<T>(n)) {
+      ok = launch_dot_tiled<T, false>(a, b, n, partials, kDotResidentBlock, dev->cus, &groups, stream);
+    } else {
+      ok = launch_dot_tiled<T, true>(a, b, n, partials, kDotBlock, dev->cus, &groups, stream);
+    }
     if (!ok) return OPAL_ERR_LAUNCH;
   }
   const double* cpartials = partials;
@@ -172,7 +267,7 @@ template <typename T>
 int launch_lds(const T* in, T* out, T c, size_t n, unsigned rep, hipStream_t stream) {
   const size_t tile = (size_t)kLdsTileVectors * (16 / sizeof(T));
   const size_t tiles = n / tile;
-  if (tiles > kMaxGrid) return OPAL_ERR_SIZE;
+  if (tiles > plan::kMaxWorkItems / kLdsBlock) return OPAL_ERR_SIZE;
   return launch(lds_stream_kernel<T, kLdsBlock>, (unsigned)tiles, (unsigned)kLdsBlock, stream, in, out, c, rep)
              ? OPAL_OK
              : OPAL_ERR_LAUNCH;
@@ -220,6 +315,29 @@ int opal_dot(const void* a, const void* b, size_t n, int dtype, void* workspace,
     return launch_dot<double>(static_cast<const double*>(a), static_cast<const double*>(b), n, partials, result, hs);
   }
   return launch_dot<float>(static_cast<const float*>(a), static_cast<const float*>(b), n, partials, result, hs);
+}
+
+void opal_set_pacing(int enabled) { g_pacing.store(enabled ? 1 : 0, std::memory_order_relaxed); }
+
+int opal_get_pacing(void) { return pacing_enabled() ? 1 : 0; }
+
+int opal_pacing_configure(int kind, double terabytes_per_second, double store_at, double second_input_at,
+                          double gap, unsigned tolerance_ticks, int feedback, unsigned set_bit) {
+  if (kind < 0 || kind > 2) return OPAL_ERR_SIZE;
+  if (!(terabytes_per_second >= 0.5 && terabytes_per_second <= 64.0)) return OPAL_ERR_SIZE;
+  if (!(store_at >= 0.0 && store_at < 1.0) || !(second_input_at >= 0.0 && second_input_at < 1.0)) return OPAL_ERR_SIZE;
+  if (!(gap >= 0.0 && gap < 0.25)) return OPAL_ERR_SIZE;
+  if (set_bit > 8 || g_shapes[kind].waves % (2u << set_bit) != 0) return OPAL_ERR_SIZE;
+  PacedShape sh = g_shapes[kind];
+  sh.bytes_per_us = terabytes_per_second * 1e6;
+  sh.store_at = store_at;
+  sh.second_input_at = second_input_at;
+  sh.gap = gap;
+  sh.set_bit = set_bit;
+  sh.tolerance = tolerance_ticks;
+  sh.feedback = feedback != 0;
+  g_shapes[kind] = sh;
+  return OPAL_OK;
 }
 
 size_t opal_lds_tile_elements(int dtype) {

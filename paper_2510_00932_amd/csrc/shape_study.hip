@@ -153,8 +153,9 @@ int main(int argc, char** argv) {
   // Dot
   const size_t tiles = nvec / (256 * 4);
   auto dot = [&](unsigned groups) {
-    dot_partial_kernel<double, 4, true, true><<<groups, 256>>>(a, b, partials, 0u, nvec, tiles, n);
-    dot_final_kernel<<<1, 256>>>(partials, groups, result);
+    const plan::Tiled t = plan::tiled(plan::Split{0u, nvec, 0u}, 256, 4, groups);
+    dot_partial_kernel<double, 4, true, true><<<t.groups, 256>>>(a, b, partials, t);
+    dot_final_kernel<<<1, 256>>>(partials, t.groups, result);
   };
   timed("dot", "dot_1_per_cu", 16.0 * n, [&] { dot((unsigned)std::min<size_t>(tiles, cus)); });
   timed("dot", "dot_8_per_cu", 16.0 * n, [&] { dot((unsigned)std::min<size_t>(tiles, (size_t)cus * 8)); });

@@ -105,6 +105,8 @@ def dot_device(a_ptr, b_ptr, n, dtype, stream=None):
     nbytes = opal.opal_dot_workspace_bytes(n, dtype)
     ws = torch.full((nbytes // 8 + 1,), float("nan"), dtype=torch.float64, device="cuda:0")
     res = torch.full((1,), float("nan"), dtype=torch.float64, device="cuda:0")
+    if stream is not None:
+        torch.cuda.synchronize()      # the fills ran on torch's stream, the kernels will not
     opal.opal_dot(a_ptr, b_ptr, n, dtype, ws.data_ptr(), nbytes, res.data_ptr(), stream)
     torch.cuda.synchronize()
     return float(res.item())

@@ -1,0 +1,135 @@
+"""Parity of the paced launch shapes (persistent wavefronts on a clock timetable, used for arrays of
+192 MiB and more) with the CPU oracle, through the C ABI.  The timetable only decides WHEN a
+wavefront issues its loads and stores, so results must be the same bits whatever the timetable:
+the default one, one that asks far too much (every wavefront always late, feedback busy), one
+that asks far too little (every wavefront waits), no feedback, and pacing switched off."""
+import numpy as np
+import pytest
+import torch
+
+import opal_inputs as oi
+import paper_2510_00932_amd as opal
+
+pytestmark = pytest.mark.gpu
+
+# kind: TB/s, store_at, second_input_at, gap, tolerance, feedback.  DEFAULTS = the library's own (launch_shapes.hpp).
+DEFAULTS = {0: (7.05, 0.75, 0.0, 0.02, 400, True), 1: (7.10, 0.0, 0.0, 0.03, 400, True), 2: (7.60, 0.0, 0.25, 0.0, 0, False)}
+TIMETABLES = {
+    "default": DEFAULTS,
+    "asks_too_much": {0: (40.0, 0.75, 0.0, 0.0, 0, True), 1: (40.0, 0.5, 0.2, 0.01, 0, True), 2: (40.0, 0.0, 0.25, 0.0, 0, True)},
+    "asks_too_little": {0: (2.5, 0.75, 0.0, 0.02, 50, True), 1: (2.5, 0.6, 0.1, 0.02, 50, True), 2: (2.5, 0.0, 0.5, 0.05, 50, True)},
+    "no_feedback_stores_free": {0: (7.0, 0.0, 0.0, 0.0, 200, False), 1: (7.1, 0.0, 0.0, 0.0, 200, False), 2: (7.6, 0.0, 0.0, 0.0, 0, False)},
+}
+
+
+def _configure(table):
+    for kind, (tb, store_at, second_at, gap, tol, fb) in table.items():
+        opal.opal_pacing_configure(kind, tb, store_at, second_at, gap, tol, fb)
+
+
+@pytest.fixture()
+def pacing():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    opal.load()
+    opal.opal_set_pacing(True)
+    yield
+    _configure(DEFAULTS)
+    opal.opal_set_pacing(True)
+
+
+@pytest.fixture(scope="module")
+def parity():
+    import parity as _parity
+    return _parity
+
+
+def _sizes(dtype):
+    # just past the 192 MiB switch, ragged; and larger, so that the rest after the last whole chunk is long
+    per = 8 if dtype == np.float64 else 4
+    return [(192 << 20) // per + 12345, (256 << 20) // per + (5 << 20) // per + 3]
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("timetable", list(TIMETABLES))
+def test_paced_chain_matches_oracle(parity, pacing, dtype, timetable):
+    _configure(TIMETABLES[timetable])
+    w = oi.workload(4)   # sign-mixed values, s = -0.75
+    n_max = max(_sizes(dtype))
+    full = [oi.uniform_array(w.seed, k, n_max, dtype, w.lo, w.hi, threads=16) for k in range(3)]
+    cases = [(_sizes(dtype)[0], (1, 1, 1)), (_sizes(dtype)[1], (0, 0, 0))]
+    if timetable == "default":
+        cases += [(_sizes(dtype)[0], (1, 2, 3)), (_sizes(dtype)[0], (0, 1, 0))]   # inputs misaligned against the output
+    for n, offsets in cases:
+        print("paced chain: %s n=%d offsets=%s timetable=%s" % (np.dtype(dtype).name, n, offsets, timetable), flush=True)
+        parity.run_chain([x[:n].copy() for x in full], w.s, offsets, check_all_arrays_each_step=False)
+        parity.run_fresh([x[:n].copy() for x in full], w.s, offsets)
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_paced_closed_forms(pacing, dtype):
+    """Ramps (every element is its own index), constants, the vector on which a fused triad differs, and dot
+    sums of integers (exact in any order, so the paced dot must hit them bit for bit)."""
+    import gpu_harness
+    import pins
+    n = _sizes(dtype)[0]
+    for offsets in [(0, 0, 0), (1, 1, 1)]:
+        impl = gpu_harness.GpuImpl(offsets)
+        pins.pin_ramp(impl, dtype, n)
+        pins.pin_constant_fill(impl, dtype, n)
+        pins.pin_fma_discriminator(impl, dtype, n=n)
+        pins.pin_dot_closed_forms(impl, dtype, [n])
+
+
+def test_pacing_off_gives_the_same_bits(pacing):
+    import gpu_harness
+    dtype = np.float64
+    n = _sizes(dtype)[0]
+    w = oi.workload(0)
+    ha, hb, hc = (oi.uniform_array(w.seed, k, n, dtype, w.lo, w.hi, threads=16) for k in range(3))
+    results = {}
+    for on in (True, False):
+        opal.opal_set_pacing(on)
+        assert opal.opal_get_pacing() == on
+        a, b, c = (gpu_harness.GuardedArray(n, dtype, 1).upload(h) for h in (ha, hb, hc))
+        torch.cuda.synchronize()
+        opal.opal_triad(a.ptr, b.ptr, c.ptr, w.s, n, opal.OPAL_F64)
+        opal.opal_copy(a.ptr, c.ptr, n, opal.OPAL_F64)
+        r = gpu_harness.dot_device(a.ptr, b.ptr, n, opal.OPAL_F64)
+        torch.cuda.synchronize()
+        assert a.guards_intact() and b.guards_intact() and c.guards_intact()
+        results[on] = (a.download(), c.download(), r)
+    assert np.array_equal(results[True][0].view(np.uint64), results[False][0].view(np.uint64))
+    assert np.array_equal(results[True][1].view(np.uint64), results[False][1].view(np.uint64))
+    # the two dot shapes add in different orders: same value to rounding, each within tolerance of the oracle
+    import oracle
+    ref = oracle.dot(results[True][0], hb)
+    for on in (True, False):
+        assert abs(results[on][2] - ref) <= 1e-12 * abs(ref)
+
+
+def test_paced_dot_is_reproducible(pacing):
+    n = _sizes(np.float64)[0]
+    ha = oi.uniform_array(5, 0, n, np.float64, -1.0, 1.0, threads=16)
+    hb = oi.uniform_array(5, 1, n, np.float64, -1.0, 1.0, threads=16)
+    a, b = torch.from_numpy(ha).cuda(), torch.from_numpy(hb).cuda()
+    res = torch.full((2,), float("nan"), dtype=torch.float64, device="cuda:0")
+    need = opal.opal_dot_workspace_bytes(n, opal.OPAL_F64)
+    ws = torch.full((need // 8,), float("nan"), dtype=torch.float64, device="cuda:0")
+    torch.cuda.synchronize()
+    opal.opal_dot(a, b, n, opal.OPAL_F64, ws, need, res.data_ptr())
+    opal.opal_dot(a, b, n, opal.OPAL_F64, ws, need, res.data_ptr() + 8)
+    torch.cuda.synchronize()
+    r = res.cpu().numpy()
+    assert r[0] == r[1]
+    import oracle
+    ref, scale = oracle.dot(ha, hb), oracle.dot_abs(ha, hb)
+    assert abs(r[0] - ref) <= 1e-12 * abs(ref), (r[0], ref, scale / abs(ref))
+
+
+def test_pacing_configure_rejects_bad_values():
+    for args in ((3, 7.0, 0.5, 0.0, 0.0, 100, 1), (-1, 7.0, 0.5, 0.0, 0.0, 100, 1), (0, 0.0, 0.5, 0.0, 0.0, 100, 1),
+                 (0, 1e9, 0.5, 0.0, 0.0, 100, 1), (0, 7.0, 1.0, 0.0, 0.0, 100, 1), (0, 7.0, -0.1, 0.0, 0.0, 100, 1),
+                 (2, 7.0, 0.0, 1.5, 0.0, 100, 1), (0, float("nan"), 0.5, 0.0, 0.0, 100, 1), (0, 7.0, 0.5, 0.0, 0.3, 100, 1), (0, 7.0, 0.5, 0.0, 0.0, 100, 1, 9)):
+        with pytest.raises(opal.OpalError) as e:
+            opal.opal_pacing_configure(*args)
+        assert e.value.status == 6
