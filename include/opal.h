@@ -100,6 +100,23 @@ size_t opal_dot_workspace_bytes(size_t n, int dtype);
 int opal_dot(const void* a, const void* b, size_t n, int dtype,
              void* workspace, size_t workspace_bytes, double* result, void* stream);
 
+/* opal_dot for callers that cannot allocate device memory or pass a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid allocation).
+ * Same kernels, same result bits as opal_dot for the same (a, b, n, dtype, device);
+ * the first pass writes its partial sums into a fixed 64 KiB array that lives in the
+ * library's device image (one copy per GPU, held until the process ends) instead of a
+ * caller workspace.  The call itself never allocates or frees; the array's device
+ * address is looked up once per device, on the first call made with that device current.
+ * opal_dot_static_scratch_bytes() is that array's size, the largest workspace any n
+ * needs; a call whose first pass would need more is refused with OPAL_ERR_WORKSPACE
+ * and enqueues nothing.  a, b, result, stream and every other rule are as for opal_dot.
+ * All calls on one GPU share the one array, which keeps the previous call's partial
+ * sums (every slot that is read is rewritten first, so nothing needs clearing):
+ * calls that may overlap on one GPU (different streams, no ordering between them)
+ * race and must be serialised by the caller. */
+size_t opal_dot_static_scratch_bytes(void);
+int opal_dot_static(const void* a, const void* b, size_t n, int dtype, double* result, void* stream);
+
 /* Launch shapes for arrays far beyond the caches ("paced" shapes).  For arrays of at least
  * 192 MiB on an MI355X the five kernels run as persistent wavefronts that issue their loads and
  * stores in bursts on a common timetable read off the chip-wide constant-rate counter, so that

@@ -19,6 +19,8 @@ from .binding import (  # noqa: F401
     opal_bytes_per_element,
     opal_copy,
     opal_dot,
+    opal_dot_static,
+    opal_dot_static_scratch_bytes,
     opal_dot_workspace_bytes,
     opal_get_pacing,
     opal_pacing_configure,

@@ -56,6 +56,10 @@ def load():
     lib.opal_dot.argtypes = [vp, vp, sz, it, vp, sz, vp, vp]
     for name in ("opal_copy", "opal_scale", "opal_add", "opal_triad", "opal_dot"):
         getattr(lib, name).restype = it
+    lib.opal_dot_static.argtypes = [vp, vp, sz, it, vp, vp]
+    lib.opal_dot_static.restype = it
+    lib.opal_dot_static_scratch_bytes.argtypes = []
+    lib.opal_dot_static_scratch_bytes.restype = sz
     lib.opal_set_pacing.argtypes = [it]
     lib.opal_set_pacing.restype = None
     lib.opal_get_pacing.argtypes = []
@@ -157,6 +161,15 @@ def opal_dot(a, b, n, dtype, workspace, workspace_bytes, result, stream=None):
     """result[0] = sum a[i]*b[i] (result: one fp64 in device memory)."""
     _check(load().opal_dot(_ptr(a), _ptr(b), n, _dtype_of(a, dtype), _ptr(workspace), workspace_bytes,
                            _ptr(result), _stream(stream)))
+
+
+def opal_dot_static_scratch_bytes() -> int:
+    return int(load().opal_dot_static_scratch_bytes())
+
+
+def opal_dot_static(a, b, n, dtype, result, stream=None):
+    """opal_dot with the partial sums in the library's own fixed device array (no workspace argument)."""
+    _check(load().opal_dot_static(_ptr(a), _ptr(b), n, _dtype_of(a, dtype), _ptr(result), _stream(stream)))
 
 
 def opal_set_pacing(enabled) -> None:

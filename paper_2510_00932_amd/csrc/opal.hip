@@ -41,10 +41,12 @@ bool launch(void (*kernel)(Params...), unsigned grid, unsigned block, hipStream_
   return hip_ok(pack(args...));
 }
 
-// Device words of the pacing feedback (pacing.hpp): a file-scope device array, one copy per GPU,
-// held until the process ends.  In host code the array's name is only a stand-in; its device
-// address comes from hipGetSymbolAddress, once per device.
+// Device words of the pacing feedback (pacing.hpp) and the scratch of opal_dot_static: file-scope
+// device arrays, one copy per GPU, held until the process ends.  In host code an array's name is
+// only a stand-in; its device address comes from hipGetSymbolAddress, once per device.
 static __device__ __align__(256) unsigned long long pace_words[kFeedbackWords];
+constexpr size_t kStaticScratchBytes = (size_t)kDotMaxGroups * sizeof(double);   // 64 KiB
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 // What the library needs to know about a device, looked up on the first call made with that
 // device current and cached by device id.
@@ -53,6 +55,7 @@ struct DeviceInfo {
   unsigned ticks_per_us = 0;              // rate of the constant counter the timetable runs on
   bool paced = false;                     // the paced shapes were measured on this kind of device
   unsigned long long* feedback = nullptr; // device address of pace_words
+  double* scratch = nullptr;              // device address of scratch
 };
 
 const DeviceInfo* device_info() {
@@ -73,6 +76,8 @@ const DeviceInfo* device_info() {
   const bool gfx950 = hip_ok(hipGetDeviceProperties(&prop, dev)) && std::strncmp(prop.gcnArchName, "gfx950", 6) == 0;
   void* ptr = nullptr;
   if (hip_ok(hipGetSymbolAddress(&ptr, HIP_SYMBOL(pace_words)))) d.feedback = static_cast<unsigned long long*>(ptr);
+  ptr = nullptr;
+  if (hip_ok(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)))) d.scratch = static_cast<double*>(ptr);
   d.paced = gfx950 && d.cus == kPacedCUs && d.ticks_per_us > 0 && d.feedback != nullptr;
   if (!slot) {
     overflow = d;
@@ -311,6 +316,27 @@ int opal_dot(const void* a, const void* b, size_t n, int dtype, void* workspace,
   if (workspace_bytes < opal_dot_workspace_bytes(n, dtype)) return OPAL_ERR_WORKSPACE;
   hipStream_t hs = static_cast<hipStream_t>(stream);
   double* partials = static_cast<double*>(workspace);
+  if (dtype == OPAL_F64) {
+    return launch_dot<double>(static_cast<const double*>(a), static_cast<const double*>(b), n, partials, result, hs);
+  }
+  return launch_dot<float>(static_cast<const float*>(a), static_cast<const float*>(b), n, partials, result, hs);
+}
+
+size_t opal_dot_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int opal_dot_static(const void* a, const void* b, size_t n, int dtype, double* result, void* stream) {
+  if (dtype != OPAL_F64 && dtype != OPAL_F32) return OPAL_ERR_DTYPE;
+  const size_t elem = dtype == OPAL_F64 ? 8 : 4;
+  int st = check_ptr(a, n, elem);
+  if (st == OPAL_OK) st = check_ptr(b, n, elem);
+  if (st != OPAL_OK) return st;
+  if (result == nullptr) return OPAL_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(result) % 8 != 0) return OPAL_ERR_ALIGN;
+  if (opal_dot_workspace_bytes(n, dtype) > kStaticScratchBytes) return OPAL_ERR_WORKSPACE;
+  const DeviceInfo* dev = device_info();
+  if (dev == nullptr || dev->scratch == nullptr) return OPAL_ERR_LAUNCH;
+  double* partials = dev->scratch;
+  hipStream_t hs = static_cast<hipStream_t>(stream);
   if (dtype == OPAL_F64) {
     return launch_dot<double>(static_cast<const double*>(a), static_cast<const double*>(b), n, partials, result, hs);
   }
