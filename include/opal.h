@@ -121,13 +121,16 @@ int opal_dot_static(const void* a, const void* b, size_t n, int dtype, double* r
  * 192 MiB on an MI355X the five kernels run as persistent wavefronts that issue their loads and
  * stores in bursts on a common timetable read off the chip-wide constant-rate counter, so that
  * HBM sees one stream and one direction at a time (about 2 % more bytes per second for the
- * elementwise kernels, 4 % for Dot, than workgroups handed out in index order).  Results are the
+ * elementwise kernels, 4 % for Dot, than workgroups handed out in index order; the switch is at
+ * 768 MiB per array for Copy and Mul, 512 MiB for Add and Triad, 384 MiB for Dot).  Results are the
  * same bits either way.  The timetable keeps a few device words of feedback inside the library's
  * device image (one copy per GPU); calls that overlap on one GPU share them, which can only cost
- * speed.  opal_set_pacing(0) switches to index-ordered workgroups for every size (the
- * environment variable OPAL_PACING=0 does the same before the first call); opal_get_pacing()
- * returns the current setting.  Process-wide, not per stream. */
-void opal_set_pacing(int enabled);
+ * speed.  opal_set_pacing(0) switches to index-ordered workgroups for every size, 1 (the
+ * default) uses the paced shapes from the sizes above on, 2 uses them for every array that holds at
+ * least 16 chunks of the timetable (128 MiB for Copy and Mul; for measurements and tests).  The
+ * environment variable OPAL_PACING=0|1|2 sets the same before the first call; opal_get_pacing()
+ * returns the current mode.  Process-wide, not per stream. */
+void opal_set_pacing(int mode);
 int opal_get_pacing(void);
 
 /* Tuning hook for the timetable of one kind of paced kernel (0: Copy and Mul, 1: Add and Triad,

@@ -172,19 +172,20 @@ def opal_dot_static(a, b, n, dtype, result, stream=None):
     _check(load().opal_dot_static(_ptr(a), _ptr(b), n, _dtype_of(a, dtype), _ptr(result), _stream(stream)))
 
 
-def opal_set_pacing(enabled) -> None:
-    load().opal_set_pacing(1 if enabled else 0)
+def opal_set_pacing(mode) -> None:
+    """0 / False: off; 1 / True: on from the library's size thresholds; 2: on wherever the shape fits."""
+    load().opal_set_pacing(int(mode))
 
 
-def opal_get_pacing() -> bool:
-    return bool(load().opal_get_pacing())
+def opal_get_pacing() -> int:
+    return int(load().opal_get_pacing())
 
 
 def opal_pacing_configure(kind, terabytes_per_second, store_at, second_input_at, gap, tolerance_ticks, feedback,
                           set_bit=3):
     _check(load().opal_pacing_configure(int(kind), float(terabytes_per_second), float(store_at),
-                                        float(second_input_at), float(gap), int(tolerance_ticks), 1 if feedback else 0,
-                                        int(set_bit)))
+                                        float(second_input_at), float(gap), int(tolerance_ticks),
+                                        1 if feedback else 0, int(set_bit)))
 
 
 def opal_lds_tile_elements(dtype) -> int:

@@ -17,12 +17,15 @@ namespace opal {
 //       sizes), tiled dot with 512-thread workgroups.  Measured crossover, chain of the five
 //       kernels back to back: temporal wins by 5-8 % up to 92 MiB per array and loses by 10 %
 //       from 128 MiB on.
-//   up to kPacedMinBytes: non-temporal accesses, wave-sized workgroups in dispatcher order, one
-//       16-byte vector per lane; tiled dot, one 256-thread workgroup per compute unit.
+//   larger, up to the paced shape's own threshold (PacedShape::min_bytes): non-temporal accesses,
+//       wave-sized workgroups in dispatcher order, one 16-byte vector per lane; tiled dot, one
+//       256-thread workgroup per compute unit.
 //   above: the paced shapes (persistent wavefronts on a clock timetable), when the device is
-//       the one the timetable was measured on; otherwise as the middle regime.
+//       the one the timetable was measured on; otherwise as the middle regime.  Measured
+//       crossover at n = 2^25 ... 2^28 fp64: Dot gains from 384 MiB per array on, Add and Triad
+//       from 512 MiB, Copy and Mul from 768 MiB; below, the ramp of the timetable (a period at
+//       each end) and its pauses cost more than the ordering gains.
 constexpr size_t kCacheResidentBytes = (size_t)96 << 20;
-constexpr size_t kPacedMinBytes = (size_t)192 << 20;
 
 constexpr int kStreamBlock = kWave;
 constexpr int kResidentBlock = 256;
@@ -46,14 +49,15 @@ struct PacedShape {
   double second_input_at;  // burst of the second input at this fraction of the period after the first
   double gap;              // accesses of a burst this fraction of the period apart (0: all at once)
   unsigned tolerance;      // ticks of lateness before reporters push the timetable back
+  size_t min_bytes;        // smallest array (bytes) the shape is used for
   bool feedback;
 };
 constexpr unsigned kPacedCUs = 256;             // the timetable is for this chip only
 constexpr int kPacedK1 = 8;                     // one-input kernels (copy, scale): K
 constexpr int kPacedK2 = 4;                     // two-input kernels (add, triad): K
 constexpr int kPacedKDot = 8;
-constexpr PacedShape kPacedOneInput = {2048, kPacedK1, 3, 7.05e6, 0.75, 0.0, 0.02, 400, true};
-constexpr PacedShape kPacedTwoInputs = {2048, kPacedK2, 3, 7.10e6, 0.0, 0.0, 0.03, 400, true};
-constexpr PacedShape kPacedDot = {1024, kPacedKDot, 3, 7.60e6, 0.0, 0.25, 0.0, 0, false};
+constexpr PacedShape kPacedOneInput = {2048, kPacedK1, 3, 7.05e6, 0.75, 0.0, 0.02, 400, (size_t)768 << 20, true};
+constexpr PacedShape kPacedTwoInputs = {2048, kPacedK2, 3, 7.10e6, 0.0, 0.0, 0.03, 400, (size_t)512 << 20, true};
+constexpr PacedShape kPacedDot = {1024, kPacedKDot, 3, 7.60e6, 0.0, 0.25, 0.0, 0, (size_t)384 << 20, false};
 
 }  // namespace opal

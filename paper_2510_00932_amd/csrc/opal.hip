@@ -90,16 +90,16 @@ const DeviceInfo* device_info() {
 
 // Run-time copies of the paced shapes (opal_pacing_configure may change the rates) and the switch.
 PacedShape g_shapes[3] = {kPacedOneInput, kPacedTwoInputs, kPacedDot};
-std::atomic<int> g_pacing{-1};   // -1: not decided yet (environment), 0: off, 1: on
+std::atomic<int> g_pacing{-1};   // -1: not decided yet (environment), 0: off, 1: on, 2: on at every size the shape can hold
 
-bool pacing_enabled() {
+int pacing_mode() {
   int v = g_pacing.load(std::memory_order_relaxed);
   if (v < 0) {
     const char* env = std::getenv("OPAL_PACING");
-    v = (env != nullptr && env[0] == '0') ? 0 : 1;
+    v = (env != nullptr && env[0] == '0') ? 0 : (env != nullptr && env[0] == '2') ? 2 : 1;
     g_pacing.store(v, std::memory_order_relaxed);
   }
-  return v != 0;
+  return v;
 }
 
 // Timetable of a paced launch: `streams` arrays, each moved waves * k KiB per period.
@@ -126,8 +126,9 @@ bool cache_resident(size_t n) { return n * sizeof(T) <= kCacheResidentBytes; }
 // The paced shapes apply to arrays well beyond the caches, on the device they were measured on.
 template <typename T>
 bool use_paced(size_t n, const DeviceInfo* dev, const PacedShape& sh) {
-  if (dev == nullptr || !dev->paced || !pacing_enabled()) return false;
-  if (n < kPacedMinBytes / sizeof(T)) return false;
+  const int mode = pacing_mode();
+  if (dev == nullptr || !dev->paced || mode == 0) return false;
+  if (mode == 1 && n < sh.min_bytes / sizeof(T)) return false;
   return n / ((size_t)(sh.waves / 2) * sh.k * (1024 / sizeof(T))) >= 16;   // at least 16 chunks
 }
 
@@ -185,7 +186,7 @@ int launch_stream(T* out, const T* in0, const T* in1, T s, size_t n, hipStream_t
   if (!size_ok<T>(n)) return OPAL_ERR_SIZE;
   if (cache_resident<T>(n)) return launch_stream_shape<T, OP, kResidentBlock, false>(out, in0, in1, s, n, stream);
   const PacedShape sh = g_shapes[kTwoInputs<OP> ? 1 : 0];
-  if (n >= kPacedMinBytes / sizeof(T)) {
+  if (pacing_mode() != 0) {
     const DeviceInfo* dev = device_info();
     if (use_paced<T>(n, dev, sh)) return launch_paced<T, OP>(out, in0, in1, s, n, *dev, sh, stream);
   }
@@ -343,9 +344,9 @@ int opal_dot_static(const void* a, const void* b, size_t n, int dtype, double* r
   return launch_dot<float>(static_cast<const float*>(a), static_cast<const float*>(b), n, partials, result, hs);
 }
 
-void opal_set_pacing(int enabled) { g_pacing.store(enabled ? 1 : 0, std::memory_order_relaxed); }
+void opal_set_pacing(int mode) { g_pacing.store(mode <= 0 ? 0 : mode >= 2 ? 2 : 1, std::memory_order_relaxed); }
 
-int opal_get_pacing(void) { return pacing_enabled() ? 1 : 0; }
+int opal_get_pacing(void) { return pacing_mode(); }
 
 int opal_pacing_configure(int kind, double terabytes_per_second, double store_at, double second_input_at,
                           double gap, unsigned tolerance_ticks, int feedback, unsigned set_bit) {

@@ -1,5 +1,5 @@
 """Parity of the paced launch shapes (persistent wavefronts on a clock timetable, used for arrays of
-192 MiB and more) with the CPU oracle, through the C ABI.  The timetable only decides WHEN a
+several hundred MiB; forced here from 128 MiB on with opal_set_pacing(2)) with the CPU oracle, through the C ABI.  The timetable only decides WHEN a
 wavefront issues its loads and stores, so results must be the same bits whatever the timetable:
 the default one, one that asks far too much (every wavefront always late, feedback busy), one
 that asks far too little (every wavefront waits), no feedback, and pacing switched off."""
@@ -31,10 +31,10 @@ def _configure(table):
 def pacing():
     assert torch.cuda.is_available(), "these tests need the MI355X"
     opal.load()
-    opal.opal_set_pacing(True)
+    opal.opal_set_pacing(2)        # paced wherever the shape fits, so that moderate sizes exercise it
     yield
     _configure(DEFAULTS)
-    opal.opal_set_pacing(True)
+    opal.opal_set_pacing(1)
 
 
 @pytest.fixture(scope="module")
@@ -44,7 +44,7 @@ def parity():
 
 
 def _sizes(dtype):
-    # just past the 192 MiB switch, ragged; and larger, so that the rest after the last whole chunk is long
+    # 24 chunks of the one-input timetable and a ragged rest; and larger, with a long rest after the last whole chunk
     per = 8 if dtype == np.float64 else 4
     return [(192 << 20) // per + 12345, (256 << 20) // per + (5 << 20) // per + 3]
 
@@ -88,8 +88,8 @@ def test_pacing_off_gives_the_same_bits(pacing):
     ha, hb, hc = (oi.uniform_array(w.seed, k, n, dtype, w.lo, w.hi, threads=16) for k in range(3))
     results = {}
     for on in (True, False):
-        opal.opal_set_pacing(on)
-        assert opal.opal_get_pacing() == on
+        opal.opal_set_pacing(2 if on else 0)
+        assert opal.opal_get_pacing() == (2 if on else 0)
         a, b, c = (gpu_harness.GuardedArray(n, dtype, 1).upload(h) for h in (ha, hb, hc))
         torch.cuda.synchronize()
         opal.opal_triad(a.ptr, b.ptr, c.ptr, w.s, n, opal.OPAL_F64)

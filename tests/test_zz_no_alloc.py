@@ -71,6 +71,7 @@ def test_static_scratch_dot_on_a_side_stream_and_misaligned(oracle):
 def test_static_scratch_dot_on_the_paced_shape_then_a_small_one(oracle):
     """An array large enough for the paced shape (1024 partial sums), then a small one (a few)."""
     opal.load()
+    opal.opal_set_pacing(2)
     for n in ((192 << 20) // 8 + 12345, 5000):
         print("opal_dot_static: paced-size check n=%d" % n, flush=True)
         ha = oi.uniform_array(13, 0, n, np.float64, 0.5, 1.5, threads=16)
@@ -80,6 +81,7 @@ def test_static_scratch_dot_on_the_paced_shape_then_a_small_one(oracle):
         assert got == want_gpu, (n, got, want_gpu)
         ref = oracle.dot(ha, hb)
         assert abs(got - ref) <= 1e-12 * abs(ref), (n, got, ref)
+    opal.opal_set_pacing(1)
 
 
 def test_static_scratch_dot_argument_errors():
