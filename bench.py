@@ -19,7 +19,6 @@ Algorithmic bytes: every input element read once and every output element writte
 (16, 16, 24, 24, 16 bytes per element in fp64; half that in fp32).
 """
 import argparse
-import hashlib
 import json
 import os
 import statistics
@@ -35,11 +34,8 @@ KERNELS = ("copy", "scale", "add", "triad", "dot")
 
 
 def kernel_source_digest():
-    h = hashlib.sha256()
-    for rel in ("paper_2510_00932_amd/csrc/stream_kernels.hpp", "paper_2510_00932_amd/csrc/launch_shapes.hpp"):
-        with open(os.path.join(ROOT, rel), "rb") as f:
-            h.update(f.read())
-    return h.hexdigest()[:16]
+    from paper_2510_00932_amd.build import kernel_source_digest as digest
+    return digest()
 
 
 def measured_traffic(workload_name, kernel):
@@ -247,7 +243,7 @@ def lds_bench(args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="n2p28_f64", help="name or index of a workload in opal_inputs.WORKLOADS")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing and the result check")
@@ -291,6 +287,8 @@ def main():
         print("bench.py: no GPU visible; the kernels have no CPU fallback", file=sys.stderr)
         sys.exit(2)
     opal.load()
+    from paper_2510_00932_amd import build as lib_build
+    assert not lib_build.is_stale(), "libopal.so does not match the sources in this tree"
 
     wl = oi.workload(int(args.workload) if args.workload.isdigit() else args.workload)
     offsets = None
@@ -421,6 +419,8 @@ def main():
         "frac_of_hbm_peak": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "kernels": kernels,
         "roofline": roofline,
+        "library": {"source_digest": lib_build.source_digest(), "kernel_source_digest": kernel_source_digest(),
+                    "pacing_mode": opal.opal_get_pacing()},
     }
 
     if not args.no_cpu_baseline:

@@ -30,7 +30,8 @@ def lib_path() -> str:
 
 
 def load():
-    """Load libopal.so (building it first only if no built library exists). Never falls back."""
+    """Load libopal.so (building it first only if no built library exists; refusing a library that was
+    built from other sources than the present ones). Never falls back."""
     global _LIB
     if _LIB is not None:
         return _LIB
@@ -45,8 +46,9 @@ def load():
     if not os.path.exists(path):
         _build.build(force=True)
     elif _build.is_stale():
-        import warnings
-        warnings.warn("libopal.so is older than its sources; rebuild with paper_2510_00932_amd/build.py")
+        raise RuntimeError("libopal.so was built from other sources than the ones in this tree (built %s, sources %s): "
+                           "rebuild it with `python paper_2510_00932_amd/build.py`"
+                           % (_build.built_digest(), _build.source_digest()))
     lib = ctypes.CDLL(path)
     vp, sz, it, dbl = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_double
     lib.opal_copy.argtypes = [vp, vp, sz, it, vp]

@@ -1,26 +1,43 @@
-// shape_study: the launch shapes that were weighed against each other for the streaming kernels,
-// side by side, as one small program that rocprofv3 can profile (every alternative is a kernel of
-// its own name, so counters separate them).  It exists to put counter evidence behind the design
-// choices of stream_kernels.hpp; the library itself only contains the shapes that won.
+// shape_study: the launch shapes that were weighed against each other for the streaming kernels, and
+// the ceilings they are measured against, side by side, as one small program that rocprofv3 can
+// profile (every alternative is a kernel of its own name, so counters separate them).  It exists to
+// put counter evidence behind the design choices of stream_kernels.hpp / pacing.hpp; the library
+// itself only contains the shapes that won.
 //
-//   shape_study [log2_n (default 28)] [launches per variant (default 5)]
+//   shape_study [log2_n (default 28)] [launches per variant (default 9)] [group: all|ceilings|copy|triad|dot]
 //
-// fp64 only.  Alternatives for Copy and Triad (Table 1):
-//   wave64_nt        one 16-byte vector per lane, 64-lane workgroups, non-temporal   (the library's choice)
+// fp64 only.
+// Ceilings (kernels that only read or only write):
+//   read1_ordered    one array, one 16-byte vector per lane, 64-lane workgroups in index order
+//   read1_tiled      one array, persistent: one 256-thread workgroup per compute unit, 8 vectors per lane per tile
+//   read2_tiled      two arrays, 4 vectors of each per lane per tile (what a dot has to read)
+//   read2_paced      two arrays, persistent wavefronts on the clock timetable (the library's dot, first pass)
+//   write_ordered    one array written, 64-lane workgroups in index order
+//   write_tiled      one array written, persistent
+//   pair             read1_ordered of `a` on one stream while write_ordered of `c` runs on another:
+//                    what a 1:1 read/write mix reaches when reads and writes are not coupled in one wavefront
+// Copy and Triad (Table 1):
+//   wave64_nt        one vector per lane, 64-lane workgroups in index order, non-temporal (the library's shape below the paced threshold)
 //   wave64_temporal  same without the non-temporal hint
 //   block256_nt      256-lane workgroups
-//   block1024_nt     1024-lane workgroups
-//   wave64_2vec_nt   two vectors per lane (2 KiB per wavefront)
+//   wave64_2vec_nt   two vectors per lane
 //   gridstride_nt    persistent: 8 workgroups of 256 lanes per compute unit, 4 vectors per lane per step
-// and for Dot:
-//   dot_1_per_cu     persistent, one 256-thread workgroup per compute unit               (the library's choice)
-//   dot_8_per_cu     persistent, eight per compute unit
-//   dot_tile         one tile per workgroup (131072 workgroups)
+//   burst            persistent wavefronts, K loads then K stores, no timetable (K = 8 / 4, 2048 wavefronts)
+//   paced_open       the same on the clock timetable, no feedback
+//   paced_mixed      timetable and feedback, but every compute unit hosts both sets
+//   paced            timetable with feedback, whole compute units per set (the library's shape for large arrays)
+// Dot:
+//   dot_1_per_cu     tiled, one 256-thread workgroup per compute unit (the library's shape below the paced threshold)
+//   dot_8_per_cu     tiled, eight per compute unit
+//   dot_tile         one tile per workgroup
+//   dot_paced        the library's shape for large arrays
 #include <algorithm>
 #include <cstdio>
 #include <cstdlib>
+#include <cstring>
 #include <vector>
 
+#include "launch_shapes.hpp"
 #include "stream_kernels.hpp"
 
 using namespace opal;
@@ -35,6 +52,56 @@ using namespace opal;
   } while (0)
 
 namespace study {
+
+// A load must feed something the compiler cannot drop: a store that never happens.
+__device__ __forceinline__ void keep(d2_t x, double* sink) {
+  if (x[0] == -1.2345e300) sink[0] = x[1];
+}
+
+__global__ __launch_bounds__(64) void read1_ordered(const double* __restrict__ a, double* __restrict__ sink) {
+  const size_t e0 = wave_uniform((size_t)blockIdx.x * 128);
+  keep(load16<double, true, true>(a + e0 + threadIdx.x * 2), sink);
+}
+
+__global__ __launch_bounds__(64) void write_ordered(double* __restrict__ c, double v) {
+  const size_t e0 = wave_uniform((size_t)blockIdx.x * 128);
+  store16<double, true>(c + e0 + threadIdx.x * 2, d2_t{v, v});
+}
+
+// Persistent: workgroup g takes tiles g, g + G, ... of blockDim.x * U vectors; U * STREAMS = 8 loads in
+// flight per lane (32 KiB per compute unit) in both cases.
+template <int STREAMS>
+__global__ __launch_bounds__(256) void read_tiled(const double* __restrict__ a, const double* __restrict__ b,
+                                                  double* __restrict__ sink, size_t nvec) {
+  constexpr int U = 8 / STREAMS;
+  const size_t tile_vecs = (size_t)blockDim.x * U;
+  const size_t tiles = nvec / tile_vecs;
+  d2_t acc = {0.0, 0.0};
+  for (size_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+    const size_t e0 = wave_uniform(tile * tile_vecs * 2);
+    d2_t x[U], y[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const unsigned e = (threadIdx.x + u * blockDim.x) * 2;
+      x[u] = load16<double, true, true>(a + e0 + e);
+      y[u] = STREAMS == 2 ? load16<double, true, true>(b + e0 + e) : x[u];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) acc += x[u] * y[u];
+  }
+  keep(acc, sink);
+}
+
+__global__ __launch_bounds__(256) void write_tiled(double* __restrict__ c, double v, size_t nvec) {
+  constexpr int U = 8;
+  const size_t tile_vecs = (size_t)blockDim.x * U;
+  const size_t tiles = nvec / tile_vecs;
+  for (size_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+    const size_t e0 = wave_uniform(tile * tile_vecs * 2);
+#pragma unroll
+    for (int u = 0; u < U; ++u) store16<double, true>(c + e0 + (threadIdx.x + u * blockDim.x) * 2, d2_t{v, v});
+  }
+}
 
 // Two vectors per lane, wave-sized workgroups (what "more bytes in flight per wavefront" costs).
 template <Op OP>
@@ -81,6 +148,13 @@ __global__ __launch_bounds__(256) void gridstride_nt(double* __restrict__ out, c
   }
 }
 
+// The library's paced kernels under names of their own per variant, so that profiles tell them apart.
+template <Op OP, int K, int VARIANT>
+__global__ __launch_bounds__(64) void paced_variant(double* out, const double* in0, const double* in1, double s,
+                                                    plan::Paced p, Pace pace) {
+  paced_stream_body<double, OP, K, true>(out, in0, in1, s, p, pace);
+}
+
 __global__ void fill(double* p, size_t n) {
   for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
     p[i] = 0.5 + (double)(i & 1023) * 9.765625e-4;
@@ -88,13 +162,28 @@ __global__ void fill(double* p, size_t n) {
 
 }  // namespace study
 
+static Pace make_pace(const PacedShape& sh, unsigned streams, bool timetable, bool feedback, unsigned long long* words) {
+  Pace pace{};
+  if (!timetable) return pace;   // period 0: no clock use at all
+  const double bytes = (double)sh.waves * sh.k * 1024.0 * streams;
+  pace.period = (uint32_t)(bytes / sh.bytes_per_us * 100.0 + 0.5);   // 100 ticks per microsecond
+  pace.second_input = (uint32_t)(sh.second_input_at * pace.period);
+  pace.store = (uint32_t)(sh.store_at * pace.period);
+  pace.gap = (uint32_t)(sh.gap * pace.period);
+  pace.tolerance = sh.tolerance;
+  pace.feedback = feedback ? words : nullptr;
+  return pace;
+}
+
 int main(int argc, char** argv) {
   const int lg = argc > 1 ? atoi(argv[1]) : 28;
-  const int launches = argc > 2 ? atoi(argv[2]) : 5;
-  if (lg < 16 || lg > 30 || launches < 1) {
-    fprintf(stderr, "usage: shape_study [log2_n 16..30] [launches >= 1]\n");
+  const int launches = argc > 2 ? atoi(argv[2]) : 9;
+  const char* group = argc > 3 ? argv[3] : "all";
+  if (lg < 24 || lg > 30 || launches < 1) {
+    fprintf(stderr, "usage: shape_study [log2_n 24..30] [launches >= 1] [all|ceilings|copy|triad|dot]\n");
     return 2;
   }
+  auto want = [&](const char* g) { return !strcmp(group, "all") || !strcmp(group, g); };
   const size_t n = (size_t)1 << lg, nvec = n / 2, bytes = n * 8, skew = 1024;
   int cus = 0;
   CHECK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, 0));
@@ -104,16 +193,33 @@ int main(int argc, char** argv) {
   double* b = (double*)(pool + bytes + skew);
   double* c = (double*)(pool + 2 * (bytes + skew));
   double *partials = nullptr, *result = nullptr;
+  unsigned long long* words = nullptr;
   CHECK(hipMalloc(&partials, (size_t)8 << 20));
   CHECK(hipMalloc(&result, 8));
+  CHECK(hipMalloc(&words, kFeedbackWords * 8));
+  CHECK(hipMemset(words, 0, kFeedbackWords * 8));
   study::fill<<<4096, 256>>>((double*)pool, 3 * (bytes + skew) / 8);
   CHECK(hipDeviceSynchronize());
-  hipEvent_t e0, e1;
+  hipEvent_t e0, e1, e2;
   CHECK(hipEventCreate(&e0));
   CHECK(hipEventCreate(&e1));
+  CHECK(hipEventCreate(&e2));
+  hipStream_t sa, sb;
+  CHECK(hipStreamCreate(&sa));
+  CHECK(hipStreamCreate(&sb));
 
-  printf("n = 2^%d fp64, %d compute units, %d launches per variant (median reported)\n", lg, cus, launches);
-  printf("%-8s %-18s %12s %10s %8s\n", "kernel", "variant", "time us", "GB/s", "of peak");
+  printf("n = 2^%d fp64, %d compute units, %d launches per variant\n", lg, cus, launches);
+  printf("%-8s %-16s %10s %10s %8s %8s %10s\n", "kernel", "variant", "median us", "GB/s", "of peak", "mean", "max us");
+  auto report = [&](const char* kernel, const char* variant, double bytes_moved, std::vector<float>& ms) {
+    double mean = 0;
+    for (float t : ms) mean += t;
+    mean /= ms.size();
+    std::sort(ms.begin(), ms.end());
+    const double us = ms[ms.size() / 2] * 1e3;
+    printf("%-8s %-16s %10.1f %10.0f %7.1f%% %7.1f%% %10.1f\n", kernel, variant, us, bytes_moved / us / 1e3,
+           bytes_moved / us / 1e3 / 80.0, bytes_moved / (mean * 1e3) / 1e3 / 80.0, ms.back() * 1e3);
+    fflush(stdout);
+  };
   auto timed = [&](const char* kernel, const char* variant, double bytes_moved, auto&& launch) {
     std::vector<float> ms;
     launch();
@@ -127,39 +233,99 @@ int main(int argc, char** argv) {
       ms.push_back(t);
     }
     CHECK(hipGetLastError());
-    std::sort(ms.begin(), ms.end());
-    const double us = ms[ms.size() / 2] * 1e3;
-    printf("%-8s %-18s %12.1f %10.0f %7.1f%%\n", kernel, variant, us, bytes_moved / us / 1e3, bytes_moved / us / 1e3 / 80.0);
-    fflush(stdout);
+    report(kernel, variant, bytes_moved, ms);
   };
 
   const double s = 0.4;
   const unsigned g64 = (unsigned)((nvec + 63) / 64), g256 = (unsigned)((nvec + 255) / 256),
-                 g1024 = (unsigned)((nvec + 1023) / 1024), g2 = (unsigned)((nvec + 127) / 128);
-  // Copy: c = a
-  timed("copy", "wave64_nt", 16.0 * n, [&] { stream_kernel<double, Op::Copy, 64, true, true><<<g64, 64>>>(c, a, nullptr, s, 0u, nvec, n); });
-  timed("copy", "wave64_temporal", 16.0 * n, [&] { stream_kernel<double, Op::Copy, 64, true, false><<<g64, 64>>>(c, a, nullptr, s, 0u, nvec, n); });
-  timed("copy", "block256_nt", 16.0 * n, [&] { stream_kernel<double, Op::Copy, 256, true, true><<<g256, 256>>>(c, a, nullptr, s, 0u, nvec, n); });
-  timed("copy", "block1024_nt", 16.0 * n, [&] { stream_kernel<double, Op::Copy, 1024, true, true><<<g1024, 1024>>>(c, a, nullptr, s, 0u, nvec, n); });
-  timed("copy", "wave64_2vec_nt", 16.0 * n, [&] { study::wave64_2vec_nt<Op::Copy><<<g2, 64>>>(c, a, nullptr, s, nvec); });
-  timed("copy", "gridstride_nt", 16.0 * n, [&] { study::gridstride_nt<Op::Copy><<<cus * 8, 256>>>(c, a, nullptr, s, nvec); });
-  // Triad: a = b + s * c
-  timed("triad", "wave64_nt", 24.0 * n, [&] { stream_kernel<double, Op::Triad, 64, true, true><<<g64, 64>>>(a, b, c, s, 0u, nvec, n); });
-  timed("triad", "wave64_temporal", 24.0 * n, [&] { stream_kernel<double, Op::Triad, 64, true, false><<<g64, 64>>>(a, b, c, s, 0u, nvec, n); });
-  timed("triad", "block256_nt", 24.0 * n, [&] { stream_kernel<double, Op::Triad, 256, true, true><<<g256, 256>>>(a, b, c, s, 0u, nvec, n); });
-  timed("triad", "block1024_nt", 24.0 * n, [&] { stream_kernel<double, Op::Triad, 1024, true, true><<<g1024, 1024>>>(a, b, c, s, 0u, nvec, n); });
-  timed("triad", "wave64_2vec_nt", 24.0 * n, [&] { study::wave64_2vec_nt<Op::Triad><<<g2, 64>>>(a, b, c, s, nvec); });
-  timed("triad", "gridstride_nt", 24.0 * n, [&] { study::gridstride_nt<Op::Triad><<<cus * 8, 256>>>(a, b, c, s, nvec); });
-  // Dot
-  const size_t tiles = nvec / (256 * 4);
-  auto dot = [&](unsigned groups) {
-    const plan::Tiled t = plan::tiled(plan::Split{0u, nvec, 0u}, 256, 4, groups);
-    dot_partial_kernel<double, 4, true, true><<<t.groups, 256>>>(a, b, partials, t);
-    dot_final_kernel<<<1, 256>>>(partials, t.groups, result);
-  };
-  timed("dot", "dot_1_per_cu", 16.0 * n, [&] { dot((unsigned)std::min<size_t>(tiles, cus)); });
-  timed("dot", "dot_8_per_cu", 16.0 * n, [&] { dot((unsigned)std::min<size_t>(tiles, (size_t)cus * 8)); });
-  timed("dot", "dot_tile", 16.0 * n, [&] { dot((unsigned)tiles); });
+                 g2 = (unsigned)((nvec + 127) / 128);
+  const plan::Split whole{0u, nvec, 0u};
+
+  if (want("ceilings")) {
+    timed("read", "read1_ordered", 8.0 * n, [&] { study::read1_ordered<<<g64, 64>>>(a, result); });
+    timed("read", "read1_tiled", 8.0 * n, [&] { study::read_tiled<1><<<cus, 256>>>(a, b, result, nvec); });
+    timed("read", "read2_tiled", 16.0 * n, [&] { study::read_tiled<2><<<cus, 256>>>(a, b, result, nvec); });
+    {
+      const plan::Paced p = plan::paced(whole, kPacedDot.waves, kPacedKDot, kPacedDot.set_bit);
+      const Pace pace = make_pace(kPacedDot, 2, true, false, words);
+      timed("read", "read2_paced", 16.0 * n, [&] { paced_dot_kernel<double, kPacedKDot, true><<<kPacedDot.waves, 64>>>(a, b, partials, p, pace); });
+    }
+    timed("write", "write_ordered", 8.0 * n, [&] { study::write_ordered<<<g64, 64>>>(c, 1.5); });
+    timed("write", "write_tiled", 8.0 * n, [&] { study::write_tiled<<<cus, 256>>>(c, 1.5, nvec); });
+    // a read-only and a write-only kernel at the same time, on two streams of equal priority
+    std::vector<float> ms;
+    for (int i = 0; i < launches + 1; ++i) {
+      CHECK(hipDeviceSynchronize());
+      CHECK(hipEventRecord(e0, sa));
+      CHECK(hipStreamWaitEvent(sb, e0, 0));
+      study::read1_ordered<<<g64, 64, 0, sa>>>(a, result);
+      study::write_ordered<<<g64, 64, 0, sb>>>(c, 1.5);
+      CHECK(hipEventRecord(e1, sa));
+      CHECK(hipEventRecord(e2, sb));
+      CHECK(hipEventSynchronize(e1));
+      CHECK(hipEventSynchronize(e2));
+      float ta, tb;
+      CHECK(hipEventElapsedTime(&ta, e0, e1));
+      CHECK(hipEventElapsedTime(&tb, e0, e2));
+      if (i) ms.push_back(std::max(ta, tb));
+    }
+    report("1R:1W", "pair", 16.0 * n, ms);
+    CHECK(hipDeviceSynchronize());
+    study::fill<<<4096, 256>>>((double*)pool, 3 * (bytes + skew) / 8);
+    CHECK(hipDeviceSynchronize());
+  }
+
+  if (want("copy")) {
+    timed("copy", "wave64_nt", 16.0 * n, [&] { stream_kernel<double, Op::Copy, 64, true, true><<<g64, 64>>>(c, a, nullptr, s, 0u, nvec, n); });
+    timed("copy", "wave64_temporal", 16.0 * n, [&] { stream_kernel<double, Op::Copy, 64, true, false><<<g64, 64>>>(c, a, nullptr, s, 0u, nvec, n); });
+    timed("copy", "block256_nt", 16.0 * n, [&] { stream_kernel<double, Op::Copy, 256, true, true><<<g256, 256>>>(c, a, nullptr, s, 0u, nvec, n); });
+    timed("copy", "wave64_2vec_nt", 16.0 * n, [&] { study::wave64_2vec_nt<Op::Copy><<<g2, 64>>>(c, a, nullptr, s, nvec); });
+    timed("copy", "gridstride_nt", 16.0 * n, [&] { study::gridstride_nt<Op::Copy><<<cus * 8, 256>>>(c, a, nullptr, s, nvec); });
+    const PacedShape sh = kPacedOneInput;
+    const plan::Paced p = plan::paced(whole, sh.waves, kPacedK1, sh.set_bit);
+    const plan::Paced pmixed = plan::paced(whole, sh.waves, kPacedK1, 8);
+    const Pace none = make_pace(sh, 2, false, false, words), open = make_pace(sh, 2, true, false, words),
+               closed = make_pace(sh, 2, true, true, words);
+    timed("copy", "burst", 16.0 * n, [&] { study::paced_variant<Op::Copy, kPacedK1, 0><<<sh.waves, 64>>>(c, a, nullptr, s, p, none); });
+    timed("copy", "paced_open", 16.0 * n, [&] { study::paced_variant<Op::Copy, kPacedK1, 1><<<sh.waves, 64>>>(c, a, nullptr, s, p, open); });
+    timed("copy", "paced_mixed", 16.0 * n, [&] { study::paced_variant<Op::Copy, kPacedK1, 2><<<sh.waves, 64>>>(c, a, nullptr, s, pmixed, closed); });
+    timed("copy", "paced", 16.0 * n, [&] { paced_stream_kernel<double, Op::Copy, kPacedK1, true><<<sh.waves, 64>>>(c, a, nullptr, s, p, closed); });
+  }
+
+  if (want("triad")) {
+    timed("triad", "wave64_nt", 24.0 * n, [&] { stream_kernel<double, Op::Triad, 64, true, true><<<g64, 64>>>(a, b, c, s, 0u, nvec, n); });
+    timed("triad", "wave64_temporal", 24.0 * n, [&] { stream_kernel<double, Op::Triad, 64, true, false><<<g64, 64>>>(a, b, c, s, 0u, nvec, n); });
+    timed("triad", "block256_nt", 24.0 * n, [&] { stream_kernel<double, Op::Triad, 256, true, true><<<g256, 256>>>(a, b, c, s, 0u, nvec, n); });
+    timed("triad", "wave64_2vec_nt", 24.0 * n, [&] { study::wave64_2vec_nt<Op::Triad><<<g2, 64>>>(a, b, c, s, nvec); });
+    timed("triad", "gridstride_nt", 24.0 * n, [&] { study::gridstride_nt<Op::Triad><<<cus * 8, 256>>>(a, b, c, s, nvec); });
+    const PacedShape sh = kPacedTwoInputs;
+    const plan::Paced p = plan::paced(whole, sh.waves, kPacedK2, sh.set_bit);
+    const plan::Paced pmixed = plan::paced(whole, sh.waves, kPacedK2, 8);
+    const Pace none = make_pace(sh, 3, false, false, words), open = make_pace(sh, 3, true, false, words),
+               closed = make_pace(sh, 3, true, true, words);
+    timed("triad", "burst", 24.0 * n, [&] { study::paced_variant<Op::Triad, kPacedK2, 0><<<sh.waves, 64>>>(a, b, c, s, p, none); });
+    timed("triad", "paced_open", 24.0 * n, [&] { study::paced_variant<Op::Triad, kPacedK2, 1><<<sh.waves, 64>>>(a, b, c, s, p, open); });
+    timed("triad", "paced_mixed", 24.0 * n, [&] { study::paced_variant<Op::Triad, kPacedK2, 2><<<sh.waves, 64>>>(a, b, c, s, pmixed, closed); });
+    timed("triad", "paced", 24.0 * n, [&] { paced_stream_kernel<double, Op::Triad, kPacedK2, true><<<sh.waves, 64>>>(a, b, c, s, p, closed); });
+  }
+
+  if (want("dot")) {
+    auto dot = [&](unsigned groups) {
+      const plan::Tiled t = plan::tiled(whole, 256, 4, groups);
+      dot_partial_kernel<double, 4, true, true><<<t.groups, 256>>>(a, b, partials, t);
+      dot_final_kernel<<<1, 256>>>(partials, t.groups, result);
+    };
+    const size_t tiles = nvec / (256 * 4);
+    timed("dot", "dot_1_per_cu", 16.0 * n, [&] { dot((unsigned)std::min<size_t>(tiles, cus)); });
+    timed("dot", "dot_8_per_cu", 16.0 * n, [&] { dot((unsigned)std::min<size_t>(tiles, (size_t)cus * 8)); });
+    timed("dot", "dot_tile", 16.0 * n, [&] { dot((unsigned)tiles); });
+    const plan::Paced p = plan::paced(whole, kPacedDot.waves, kPacedKDot, kPacedDot.set_bit);
+    const Pace pace = make_pace(kPacedDot, 2, true, false, words);
+    timed("dot", "dot_paced", 16.0 * n, [&] {
+      paced_dot_kernel<double, kPacedKDot, true><<<kPacedDot.waves, 64>>>(a, b, partials, p, pace);
+      dot_final_kernel<<<1, 256>>>(partials, kPacedDot.waves, result);
+    });
+  }
   CHECK(hipDeviceSynchronize());
   return 0;
 }

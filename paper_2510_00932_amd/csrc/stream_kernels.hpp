@@ -180,8 +180,9 @@ __global__ __launch_bounds__(BLOCK) void stream_kernel(
 // Paced elementwise kernel: gridDim.x = p.waves one-wavefront workgroups (see the file header).
 // Same pointer and alignment conventions as stream_kernel; all accesses non-temporal.
 template <typename T, Op OP, int K, bool ALIGNED>
-__global__ __launch_bounds__(kWave) void paced_stream_kernel(
-    T* __restrict__ out, const T* __restrict__ in0, const T* __restrict__ in1, T s, plan::Paced p, Pace pace) {
+__device__ __forceinline__ void paced_stream_body(
+    T* __restrict__ out, const T* __restrict__ in0, const T* __restrict__ in1, T s, const plan::Paced& p,
+    const Pace& pace) {
   typedef typename Vec16<T>::type V;
   constexpr int L = Vec16<T>::lanes;
   constexpr unsigned RUN = plan::kRunVectors * L;   // elements per run
@@ -250,6 +251,12 @@ __global__ __launch_bounds__(kWave) void paced_stream_kernel(
     }
   }
   if (wave == p.waves - 1) edge_elements<T, OP>(out, in0, in1, s, p.split, lane, kWave);
+}
+
+template <typename T, Op OP, int K, bool ALIGNED>
+__global__ __launch_bounds__(kWave) void paced_stream_kernel(
+    T* __restrict__ out, const T* __restrict__ in0, const T* __restrict__ in1, T s, plan::Paced p, Pace pace) {
+  paced_stream_body<T, OP, K, ALIGNED>(out, in0, in1, s, p, pace);
 }
 
 // ---------------------------------------------------------------------------

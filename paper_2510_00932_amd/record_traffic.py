@@ -13,25 +13,26 @@ A text summary is printed on stdout.
 """
 import csv
 import glob
-import hashlib
 import json
 import os
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
 CAL_BYTES = 1 << 30
 CAL_KERNEL = "__amd_rocclr_copyBuffer"
-KERNEL_KEYS = (("copy", "(opal::Op)0"), ("scale", "(opal::Op)1"), ("add", "(opal::Op)2"),
-               ("triad", "(opal::Op)3"), ("dot", "dot_partial_kernel"), ("dot_final", "dot_final_kernel"))
+# kernel names as rocprofv3 prints them; the elementwise and the dot first-pass kernels exist in an
+# index-ordered / tiled and a paced form, of which a run uses one per workload
+KERNEL_KEYS = (("copy", "stream_kernel", "(opal::Op)0"), ("scale", "stream_kernel", "(opal::Op)1"),
+               ("add", "stream_kernel", "(opal::Op)2"), ("triad", "stream_kernel", "(opal::Op)3"),
+               ("dot", "dot_", "_kernel"), ("dot_final", "dot_final_kernel", ""))
 
 
 def source_digest():
-    h = hashlib.sha256()
-    for rel in ("paper_2510_00932_amd/csrc/stream_kernels.hpp", "paper_2510_00932_amd/csrc/launch_shapes.hpp"):
-        with open(os.path.join(ROOT, rel), "rb") as f:
-            h.update(f.read())
-    return h.hexdigest()[:16]
+    from paper_2510_00932_amd.build import kernel_source_digest
+    return kernel_source_digest()
 
 
 def per_kernel(dirname, counter):
@@ -46,10 +47,11 @@ def per_kernel(dirname, counter):
     return vals
 
 
-def pick(vals, needle):
-    hits = [v for k, v in vals.items() if needle in k]
+def pick(vals, *needles):
+    hits = [v for k, v in vals.items() if all(x in k for x in needles)
+            and not (needles[0] == "dot_" and "dot_final" in k)]
     if len(hits) != 1:
-        raise SystemExit("kernel %r: expected one match, found %d" % (needle, len(hits)))
+        raise SystemExit("kernel %r: expected one match, found %d" % (needles, len(hits)))
     return sum(hits[0]) / len(hits[0]), len(hits[0])
 
 
@@ -67,9 +69,9 @@ def main():
     print("%-10s %14s %14s %16s %16s %16s %9s" % ("kernel", "FETCH_SIZE", "WRITE_SIZE", "fetched bytes", "written bytes",
                                                    "HBM bytes", "launches"))
     out = {}
-    for name, needle in KERNEL_KEYS:
-        f_avg, nf = pick(fetch, needle)
-        w_avg, _ = pick(write, needle)
+    for name, *needles in KERNEL_KEYS:
+        f_avg, nf = pick(fetch, *needles)
+        w_avg, _ = pick(write, *needles)
         fb, wb = f_avg * bytes_per_fetch_unit, w_avg * bytes_per_write_unit
         out[name] = int(round(fb + wb))
         print("%-10s %14.1f %14.1f %16.0f %16.0f %16.0f %9d" % (name, f_avg, w_avg, fb, wb, fb + wb, nf))

@@ -13,8 +13,10 @@ observed and peak values), applied to this library's own kernels and without the
   *_counter_collection.csv  from  rocprofv3 --pmc <counters> -- python3 bench.py ... [--calibration-copy]
 Any subset of counters may be present; lines whose counters are missing are left out.
 
-Peaks (MI355X, published): HBM 8.0 TB/s; vector fp64 78.6 TFLOP/s, fp32 157.3 TFLOP/s;
-256 compute units at 2.4 GHz.
+Peaks (MI355X): HBM 8.0 TB/s and vector fp64 78.6 / fp32 157.3 TFLOP/s are published; the cache
+levels are derived from unit counts, widths per clock and the 2.4 GHz peak clock: L2 = 8 XCDs x 16
+channels x 128 B/clk = 39.3 TB/s; L1 (vector cache to L2 and to the compute unit) = 256 compute
+units x 64 B/clk = 39.3 TB/s; LDS = 256 compute units x 128 B/clk = 78.6 TB/s.
 """
 import argparse
 import csv
@@ -25,17 +27,23 @@ import sys
 HBM_PEAK = 8.0e12
 VALU_PEAK = {"f64": 78.6e12, "f32": 157.3e12}
 CLOCK_HZ = 2.4e9
+L2_PEAK = 8 * 16 * 128 * CLOCK_HZ       # bytes per second
+L1_PEAK = 256 * 64 * CLOCK_HZ
+LDS_PEAK = 256 * 128 * CLOCK_HZ
 CAL_KERNEL = "__amd_rocclr_copyBuffer"
 CAL_BYTES = 1 << 30
 
-# name, substring of the kernel's symbol, algorithmic bytes per element in units of the element size, flops per element
+# name, substrings of the kernel's symbol, algorithmic bytes per element in units of the element size, flops per
+# element.  The elementwise kernels and dot's first pass exist in an index-ordered / tiled and a paced form; a run
+# uses one of them per workload.
 KERNELS = (
-    ("copy", "(opal::Op)0", 2, 0),
-    ("scale", "(opal::Op)1", 2, 1),
-    ("add", "(opal::Op)2", 3, 1),
-    ("triad", "(opal::Op)3", 3, 2),
-    ("dot", "dot_partial_kernel", 2, 2),
+    ("copy", ("stream_kernel", "(opal::Op)0"), 2, 0),
+    ("scale", ("stream_kernel", "(opal::Op)1"), 2, 1),
+    ("add", ("stream_kernel", "(opal::Op)2"), 3, 1),
+    ("triad", ("stream_kernel", "(opal::Op)3"), 3, 2),
+    ("dot", ("dot_", "_kernel<"), 2, 2),
 )
+LDS_KERNEL = ("lds_stream_kernel",)
 
 
 def find(root, suffix):
@@ -62,8 +70,10 @@ def read_counters(root):
     return {c: {k: sum(v) / len(v) for k, v in per.items()} for c, per in acc.items()}
 
 
-def pick(table, needle):
-    hits = [v for k, v in table.items() if needle in k]
+def pick(table, needles):
+    if isinstance(needles, str):
+        needles = (needles,)
+    hits = [v for k, v in table.items() if all(x in k for x in needles)]
     return hits[0] if len(hits) == 1 else None
 
 
@@ -124,6 +134,25 @@ def analyse(root, n, dtype):
         tlb_req, tlb_miss = ctr("TCP_UTCL1_REQUEST_sum", needle), ctr("TCP_UTCL1_TRANSLATION_MISS_sum", needle)
         if tlb_req and tlb_miss is not None:
             m["tlb_miss_rate"] = tlb_miss / tlb_req
+        # traffic per cache level, from request counts (the request size is what the counters cannot tell: it is
+        # inferred from the algorithmic bytes, which every level moves exactly once in these kernels)
+        if "seconds" in m:
+            l2req = ctr("TCC_REQ_sum", needle)
+            if l2req:
+                m["l2_bytes_per_request"] = alg_bytes / l2req
+                m["l2_bytes_per_s"] = alg_bytes / m["seconds"]
+                m["l2_frac"] = m["l2_bytes_per_s"] / L2_PEAK
+            l1rd, l1wr = ctr("TCP_TCC_READ_REQ_sum", needle), ctr("TCP_TCC_WRITE_REQ_sum", needle)
+            if l1rd is not None and l1wr is not None and (l1rd + l1wr) > 0:
+                m["l1_l2_bytes_per_request"] = alg_bytes / (l1rd + l1wr)
+                m["l1_bytes_per_s"] = alg_bytes / m["seconds"]
+                m["l1_frac"] = m["l1_bytes_per_s"] / L1_PEAK
+            acc, cacc = ctr("TCP_TOTAL_ACCESSES_sum", needle), ctr("TCP_TOTAL_CACHE_ACCESSES_sum", needle)
+            if acc:
+                m["l1_accesses"] = acc
+                m["l1_bytes_per_access"] = alg_bytes / acc
+            if cacc is not None:
+                m["l1_cache_accesses"] = cacc
         waves, wave_cycles = ctr("SQ_WAVES", needle), ctr("SQ_WAVE_CYCLES", needle)
         if waves and wave_cycles:
             m["wave_lifetime_cycles"] = 4.0 * wave_cycles / waves     # the counter ticks once per four cycles
@@ -143,6 +172,14 @@ def analyse(root, n, dtype):
         if "traffic_over_algorithmic" in m:
             lines.append("  HBM traffic (FETCH_SIZE + WRITE_SIZE, calibrated) = %.4f x algorithmic bytes"
                          % m["traffic_over_algorithmic"])
+        if "l2_frac" in m:
+            lines.append("  L2: %.0f GB/s = %.1f %% of its %.1f TB/s peak (%.0f bytes per L2 request)"
+                         % (m["l2_bytes_per_s"] / 1e9, 100 * m["l2_frac"], L2_PEAK / 1e12, m["l2_bytes_per_request"]))
+        if "l1_frac" in m:
+            lines.append("  L1 (vector cache to L2): %.0f GB/s = %.1f %% of its %.1f TB/s peak (%.0f bytes per request to L2)"
+                         % (m["l1_bytes_per_s"] / 1e9, 100 * m["l1_frac"], L1_PEAK / 1e12, m["l1_l2_bytes_per_request"]))
+        if "l1_bytes_per_access" in m:
+            lines.append("  L1 accesses: %.0f per launch, %.0f algorithmic bytes each" % (m["l1_accesses"], m["l1_bytes_per_access"]))
         if "l2_hit_rate" in m:
             note = " (hits are the second 64-byte half of a freshly allocated write line)" if m["l2_hit_rate"] > 0.01 else ""
             lines.append("  L2 hit rate %.1f %%%s" % (100 * m["l2_hit_rate"], note))
@@ -164,6 +201,33 @@ def analyse(root, n, dtype):
     return results, lines
 
 
+def analyse_lds(root, n, dtype, rep):
+    """The LDS microkernel: observed LDS bandwidth (32 bytes per 16-byte vector per round, from the definition, and
+    from the LDS load/store bandwidth counters where present) against the LDS peak."""
+    stats = read_kernel_stats(root)
+    counters = read_counters(root)
+    width = 8 if dtype == "f64" else 4
+    st = pick(stats, LDS_KERNEL + (("double" if dtype == "f64" else "float"),))
+    if not st:
+        return []
+    t = st[1] * 1e-9
+    lds_bytes = 32.0 * (n * width / 16) * rep
+    lines = ["", "lds_stream (n = %d %s, rep = %d)" % (n, dtype, rep),
+             "  time per launch %.1f us; LDS traffic by definition %.3e bytes -> %.0f GB/s = %.1f %% of the %.1f TB/s LDS peak"
+             % (t * 1e6, lds_bytes, lds_bytes / t / 1e9, 100 * lds_bytes / t / LDS_PEAK, LDS_PEAK / 1e12),
+             "  per compute unit and clock at 2.4 GHz: %.1f bytes (%.1f read + %.1f written)"
+             % (lds_bytes / t / 256 / CLOCK_HZ, lds_bytes / t / 256 / CLOCK_HZ / 2, lds_bytes / t / 256 / CLOCK_HZ / 2)]
+    needle = LDS_KERNEL + (("double" if dtype == "f64" else "float"),)
+    conf, idx = pick(counters.get("SQ_LDS_BANK_CONFLICT", {}), needle), pick(counters.get("SQ_LDS_IDX_ACTIVE", {}), needle)
+    if conf is not None and idx:
+        lines.append("  LDS bank conflicts: %.2f %% of LDS-active cycles" % (100 * conf / idx))
+    frac = lds_bytes / t / LDS_PEAK
+    lines.append("  => LDS is %s (%.0f %% of peak); HBM carries only one read and one write of the tile (%.3f %% of its peak)"
+                 % ("the binding component" if frac >= 0.8 else "under-used", 100 * frac,
+                    100 * 2 * n * width / t / HBM_PEAK))
+    return lines
+
+
 def verdicts(m):
     """Observed against peak, component by component: which one binds, which are under-used."""
     out = []
@@ -175,6 +239,10 @@ def verdicts(m):
         else:
             out.append("HBM is under-used (%.0f %% of peak) although the kernel is memory-bound by intensity: "
                        "look at launch shape, in-flight requests and access order" % (100 * m["hbm_frac"]))
+    for key, what in (("l2_frac", "L2"), ("l1_frac", "L1")):
+        if key in m and m[key] < 0.5:
+            out.append("%s is under-used (%.0f %% of its peak): every byte passes through it once, nothing is reused, "
+                       "so it can only ever carry the HBM rate" % (what, 100 * m[key]))
     if m.get("traffic_over_algorithmic", 1.0) > 1.02:
         out.append("HBM moves %.1f %% more than the algorithm needs: re-reads or partial-line writes"
                    % (100 * (m["traffic_over_algorithmic"] - 1)))
@@ -193,8 +261,12 @@ def main():
     ap.add_argument("dir")
     ap.add_argument("--n", type=int, default=1 << 28)
     ap.add_argument("--dtype", choices=("f64", "f32"), default="f64")
+    ap.add_argument("--lds-n", type=int, default=0, help="element count of the LDS microkernel launches in the run (0: none)")
+    ap.add_argument("--lds-rep", type=int, default=600)
     args = ap.parse_args()
     _, lines = analyse(args.dir, args.n, args.dtype)
+    if args.lds_n:
+        lines += analyse_lds(args.dir, args.lds_n, args.dtype, args.lds_rep)
     print("\n".join(lines))
 
 

@@ -106,3 +106,59 @@ def test_binding_refuses_host_tensors():
     t = torch.zeros(4, dtype=torch.float64)
     with pytest.raises(TypeError):
         opal.opal_copy(t, t, 4)
+
+
+def _no_gpu():
+    import torch
+    return not torch.cuda.is_available()
+
+
+@pytest.mark.skipif(not _no_gpu(), reason="with a GPU present these calls would launch on made-up addresses")
+def test_runtime_failures_surface_as_err_launch_with_the_hip_error_name():
+    """Without a usable GPU the first runtime query of a call fails: the call must return OPAL_ERR_LAUNCH
+    (never crash, never report success) and opal_last_hip_error() must name the runtime's error."""
+    lib = opal.load()
+    n = 1 << 20
+    assert _status(opal.opal_copy, A, A + (n << 4), n, opal.OPAL_F64) == 5
+    name = lib.opal_last_hip_error().decode()
+    assert name.startswith("hipError") and name != "hipSuccess", name
+    need = opal.opal_dot_workspace_bytes(n, opal.OPAL_F64)
+    assert _status(opal.opal_dot, A, A + (n << 4), n, opal.OPAL_F64, A, need, A) == 5
+    assert _status(opal.opal_dot_static, A, A + (n << 4), n, opal.OPAL_F64, A) == 5
+    try:
+        opal.opal_copy(A, A + (n << 4), n, opal.OPAL_F64)
+    except opal.OpalError as e:
+        assert "hipError" in str(e)          # the binding appends the runtime's error name to status 5
+
+
+def test_sizes_whose_byte_count_does_not_fit_are_refused_before_any_gpu_call():
+    huge = 1 << 62
+    assert _status(opal.opal_copy, A, A, huge, opal.OPAL_F64) == 6
+    assert _status(opal.opal_triad, A, A, A, 0.4, huge, opal.OPAL_F64) == 6
+    assert _status(opal.opal_copy, A, A, 1 << 63, opal.OPAL_F32) == 6
+    need = opal.opal_dot_workspace_bytes(huge, opal.OPAL_F64)
+    assert _status(opal.opal_dot, A, A, huge, opal.OPAL_F64, A, need, A) == 6
+
+
+def test_dot_with_n_zero_still_needs_result_and_workspace():
+    # the pointer checks of opal_dot do not depend on n (documented in opal.h)
+    assert _status(opal.opal_dot, 0, 0, 0, opal.OPAL_F64, 0, 64, A) == 1
+    assert _status(opal.opal_dot, 0, 0, 0, opal.OPAL_F64, A, 64, 0) == 1
+
+
+def test_pacing_switch_and_tuning_hook_are_host_only():
+    lib = opal.load()
+    before = opal.opal_get_pacing()
+    for mode in (0, 1, 2):
+        opal.opal_set_pacing(mode)
+        assert opal.opal_get_pacing() == mode
+    opal.opal_set_pacing(before)
+    assert lib.opal_pacing_configure(7, 7.0, 0.5, 0.0, 0.0, 100, 1, 3) == 6
+    assert lib.opal_pacing_configure(0, 7.0, 0.5, 0.0, 0.0, 100, 1, 12) == 6
+
+
+def test_built_library_matches_the_sources():
+    from paper_2510_00932_amd import build
+    opal.load()
+    assert not build.is_stale()
+    assert build.built_digest() == build.source_digest()

@@ -62,3 +62,47 @@ def test_missing_counters_are_left_out(tmp_path):
     results, lines = rr.analyse(str(tmp_path), 1 << 28, "f64")
     m = dict(results)["copy"]
     assert "hbm_frac" in m and "l2_hit_rate" not in m and "hbm_traffic_bytes" not in m
+
+
+def _write_csvs(tmp_path, stats_rows, counter_rows):
+    with open(tmp_path / "r_kernel_stats.csv", "w") as f:
+        f.write('"Name","Calls","TotalDurationNs","AverageNs","Percentage","MinNs","MaxNs","StdDev"\n')
+        for name, avg_ns in stats_rows:
+            f.write('"%s",10,%d,%f,1.0,%d,%d,0.0\n' % (name, int(avg_ns * 10), avg_ns, int(avg_ns), int(avg_ns)))
+    with open(tmp_path / "r_counter_collection.csv", "w") as f:
+        f.write('"Kernel_Name","Counter_Name","Counter_Value"\n')
+        for name, counter, value in counter_rows:
+            f.write('"%s","%s",%f\n' % (name, counter, value))
+
+
+def test_cache_levels_are_compared_with_their_peaks(tmp_path):
+    """L2 and L1 carry the algorithmic bytes once; the report states their rate against the per-level peak
+    and the request size the counters imply, and calls both under-used."""
+    n = 1 << 28
+    paced = "void opal::paced_stream_kernel<double, (opal::Op)3, 4, true>(double*, double const*, double const*, double, opal::plan::Paced, opal::Pace)"
+    alg = 24 * n
+    _write_csvs(tmp_path, [(paced, 920000.0)],
+                [(paced, "TCC_REQ_sum", alg / 128), (paced, "TCP_TCC_READ_REQ_sum", 16 * n / 64),
+                 (paced, "TCP_TCC_WRITE_REQ_sum", 8 * n / 64), (paced, "TCP_TOTAL_ACCESSES_sum", alg / 1024)])
+    results, lines = rr.analyse(str(tmp_path), n, "f64")
+    m = dict(results)["triad"]
+    assert m["l2_bytes_per_request"] == pytest.approx(128.0) and m["l1_l2_bytes_per_request"] == pytest.approx(64.0)
+    assert m["l2_frac"] == pytest.approx(alg / 920e-6 / (8 * 16 * 128 * 2.4e9))
+    assert m["l1_frac"] == pytest.approx(alg / 920e-6 / (256 * 64 * 2.4e9))
+    text = "\n".join(lines)
+    assert "L2: " in text and "L1 (vector cache to L2)" in text
+    assert "L2 is under-used" in text and "L1 is under-used" in text
+    assert "HBM is the binding component" in text
+
+
+def test_lds_kernel_is_compared_with_the_lds_peak(tmp_path):
+    name = "void opal::lds_stream_kernel<double, 256>(double const*, double*, double, unsigned int)"
+    n, rep = 256 * 5 * 8 * 2048, 600
+    lds_bytes = 32.0 * (n * 8 / 16) * rep
+    t_ns = lds_bytes / 70.0e12 * 1e9          # 70 TB/s
+    _write_csvs(tmp_path, [(name, t_ns)], [(name, "SQ_LDS_BANK_CONFLICT", 0.0), (name, "SQ_LDS_IDX_ACTIVE", 1000.0)])
+    lines = rr.analyse_lds(str(tmp_path), n, "f64", rep)
+    text = "\n".join(lines)
+    assert "70000 GB/s" in text and "89.0 %" in text        # 70 / 78.6
+    assert "bank conflicts: 0.00 %" in text and "binding component" in text
+    assert rr.analyse_lds(str(tmp_path), n, "f32", rep) == []     # no fp32 kernel in this run
