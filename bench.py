@@ -73,11 +73,15 @@ def paper_shapes(args):
     opal.load()
     dev = torch.device("cuda:0")
     wl = oi.workload(0)
-    dt, tdt, item, s = opal.OPAL_F64, torch.float64, 8, wl.s
+    s = wl.s
     results = []
     checks = []
-    for n in (2000896, 4000768, 6000640):
-        host = oi.make_arrays(wl, n=n)
+    cases = [(n, dtype_name) for dtype_name in ("f64", "f32") for n in (2000896, 4000768, 6000640)]
+    for n, dtype_name in cases:
+        dt, tdt, item, npdt = (opal.OPAL_F64, torch.float64, 8, np.float64) if dtype_name == "f64" else \
+            (opal.OPAL_F32, torch.float32, 4, np.float32)
+        bits = np.uint64 if dtype_name == "f64" else np.uint32
+        host = [oi.uniform_array(wl.seed, k, n, npdt, wl.lo, wl.hi) for k in range(3)]
         pitch = (n * item + 255) // 256 * 256 + args.skew_bytes
         pool = torch.empty(3 * pitch + 256, dtype=torch.uint8, device=dev)
         a, b, c = (pool[k * pitch:k * pitch + n * item].view(tdt) for k in range(3))
@@ -105,9 +109,9 @@ def paper_shapes(args):
         g1 = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g1, stream=stream):
             iteration(torch.cuda.current_stream())
-        bytes_per_iter = 96 * n
+        bytes_per_iter = 12 * item * n
         for num_times in (100, 200, 300):
-            row = {"array_size": n, "num_times": num_times}
+            row = {"array_size": n, "dtype": dtype_name, "num_times": num_times}
             # eager
             reset()
             t0 = time.perf_counter()
@@ -141,7 +145,7 @@ def paper_shapes(args):
             del gall
             best = min(row["eager_us_per_iter"], row["graph_us_per_iter"], row["graph_all_us_per_iter"])
             row["best_GBps"] = round(bytes_per_iter / best / 1e3, 1)
-            same = all(np.array_equal(x.view(np.uint64), y.view(np.uint64)) and np.array_equal(x.view(np.uint64), z.view(np.uint64))
+            same = all(np.array_equal(x.view(bits), y.view(bits)) and np.array_equal(x.view(bits), z.view(bits))
                        for x, y, z in zip(final_eager[:3], final_graph[:3], final_all[:3]))
             row["three_ways_bit_identical"] = bool(same and final_eager[3] == final_graph[3] == final_all[3])
             if num_times == 100 and not args.no_cpu_baseline:
@@ -154,21 +158,74 @@ def paper_shapes(args):
                     oracle.add(xa, xb, xc)
                     oracle.triad(xa, xb, xc, s)
                     r = oracle.dot(xa, xb)
-                exact = all(np.array_equal(x.view(np.uint64), y.view(np.uint64)) for x, y in zip(final_eager[:3], (xa, xb, xc)))
+                exact = all(np.array_equal(x.view(bits), y.view(bits)) for x, y in zip(final_eager[:3], (xa, xb, xc)))
                 rel = abs(final_eager[3] - r) / abs(r)
-                checks.append({"array_size": n, "num_times": num_times, "elementwise_bit_exact": bool(exact),
-                               "dot_rel_err": float("%.3e" % rel)})
+                checks.append({"array_size": n, "dtype": dtype_name, "num_times": num_times,
+                               "elementwise_bit_exact": bool(exact), "dot_rel_err": float("%.3e" % rel),
+                               "dot_tolerance": 1e-12 if dtype_name == "f64" else 1e-5})
             results.append(row)
         del g1
     out = {"metric": "time per iteration (copy, scale, add, triad, dot) at the paper's array sizes, 1 GPU",
-           "unit": "us", "dtype": "f64", "data": "synthetic", "bytes_per_iteration": "96 * array_size",
+           "unit": "us", "dtype": "f64 and f32", "data": "synthetic", "bytes_per_iteration": "12 * element size * array_size",
            "results": results, "check_vs_oracle": checks}
     print(json.dumps(out))
     bad = [r for r in results if not r["three_ways_bit_identical"]] + \
-        [c for c in checks if not (c["elementwise_bit_exact"] and c["dot_rel_err"] <= 1e-12)]
+        [c for c in checks if not (c["elementwise_bit_exact"] and c["dot_rel_err"] <= c["dot_tolerance"])]
     if bad:
         print("bench.py: paper-shape results differ", file=sys.stderr)
         sys.exit(1)
+
+
+def call_overhead(args):
+    """Host cost of one call through the C ABI, in the regime where a kernel lasts microseconds (the paper's
+    Section 6.4 finding was a host-side cost per launch): `calls` back-to-back calls on arrays of 64 elements.
+      enqueue_us : host time per call while the queue still has room (the call itself: argument checks, the
+                   device query of opal_dot, one or two hipLaunchKernel)
+      drain_us   : wall time per call including the final synchronisation (what the GPU front end sustains)
+    Prints one JSON line."""
+    import torch
+
+    import paper_2510_00932_amd as opal
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the kernels have no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    lib = opal.load()
+    n = 64
+    a = torch.ones(n, dtype=torch.float64, device="cuda:0")
+    b = torch.ones(n, dtype=torch.float64, device="cuda:0")
+    c = torch.zeros(n, dtype=torch.float64, device="cuda:0")
+    ws = torch.zeros(16, dtype=torch.float64, device="cuda:0")
+    res = torch.zeros(1, dtype=torch.float64, device="cuda:0")
+    stream = torch.cuda.Stream()
+    hs = stream.cuda_stream
+    pa, pb, pc, pws, pres = a.data_ptr(), b.data_ptr(), c.data_ptr(), ws.data_ptr(), res.data_ptr()
+    # the raw ctypes entry points: no Python-side marshalling beyond ctypes' own
+    cases = (("opal_copy", lambda: lib.opal_copy(pa, pc, n, 0, hs), 1),
+             ("opal_triad", lambda: lib.opal_triad(pa, pb, pc, 0.4, n, 0, hs), 1),
+             ("opal_dot", lambda: lib.opal_dot(pa, pb, n, 0, pws, 128, pres, hs), 2),
+             ("opal_dot_static", lambda: lib.opal_dot_static(pa, pb, n, 0, pres, hs), 2),
+             ("opal_dot_workspace_bytes (no GPU work)", lambda: lib.opal_dot_workspace_bytes(n, 0), 0))
+    calls = 20000
+    results = []
+    for name, fn, launches in cases:
+        for _ in range(200):
+            fn()
+        stream.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(256):              # short enough that the hardware queue never fills
+            fn()
+        t_enq = (time.perf_counter() - t0) / 256
+        stream.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(calls):
+            fn()
+        stream.synchronize()
+        t_all = (time.perf_counter() - t0) / calls
+        results.append({"call": name, "kernel_launches": launches, "enqueue_us": round(t_enq * 1e6, 2),
+                        "drain_us": round(t_all * 1e6, 2)})
+    print(json.dumps({"metric": "host cost per call through the C ABI (ctypes), arrays of 64 elements, 1 GPU",
+                      "unit": "us", "calls": calls, "results": results}))
 
 
 def lds_bench(args):
@@ -258,6 +315,8 @@ def main():
     ap.add_argument("--paper-shapes", action="store_true",
                     help="instead of the roofline benchmark, time the paper's own (small, cache-resident) array "
                          "sizes and repetition counts issued eagerly and through HIP graphs")
+    ap.add_argument("--call-overhead", action="store_true",
+                    help="instead of the roofline benchmark, time the host cost of one call through the C ABI")
     ap.add_argument("--lds", action="store_true",
                     help="instead of the roofline benchmark, time the LDS-streaming microkernel (rep = 300..1500)")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -275,6 +334,9 @@ def main():
         return
     if args.lds:
         lds_bench(args)
+        return
+    if args.call_overhead:
+        call_overhead(args)
         return
 
     import numpy as np

@@ -126,6 +126,15 @@ def test_paced_dot_is_reproducible(pacing):
     assert abs(r[0] - ref) <= 1e-12 * abs(ref), (r[0], ref, scale / abs(ref))
 
 
+def test_paced_kernels_replay_from_a_hip_graph(parity, pacing):
+    """The timetable keeps its feedback in device words that outlive a launch, and tells launches apart by a
+    time stamp taken on the device: a captured paced kernel must replay like any other (same bits as the
+    oracle after every replay, eager work in between)."""
+    import gpu_harness
+    from test_gpu_parity import graph_replay_check
+    graph_replay_check(parity, gpu_harness, _sizes(np.float64)[0], np.float64, offsets=(1, 1, 1), replays=3)
+
+
 def test_pacing_configure_rejects_bad_values():
     for args in ((3, 7.0, 0.5, 0.0, 0.0, 100, 1), (-1, 7.0, 0.5, 0.0, 0.0, 100, 1), (0, 0.0, 0.5, 0.0, 0.0, 100, 1),
                  (0, 1e9, 0.5, 0.0, 0.0, 100, 1), (0, 7.0, 1.0, 0.0, 0.0, 100, 1), (0, 7.0, -0.1, 0.0, 0.0, 100, 1),

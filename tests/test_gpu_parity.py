@@ -199,16 +199,16 @@ def test_against_torch_as_a_sanity_check(harness):
 
 # ------------------------------------------------------------------ captured into a HIP graph
 
-def test_graph_replay_matches_oracle(parity, harness):
-    """The library neither allocates nor synchronises, so one pass copy -> scale -> add -> triad -> dot
-    can be captured into a HIP graph.  Every replay (with the program's own eager launches and
-    synchronisations in between) must leave exactly what that many oracle passes leave."""
+def graph_replay_check(parity, harness, n, dtype, offsets=(0, 1, 0), replays=5):
+    """One pass copy -> scale -> add -> triad -> dot, eager, then captured into a HIP graph and replayed.
+    Every replay (with the program's own eager launches and synchronisations in between) must leave
+    exactly what that many oracle passes leave."""
     import oracle
     w = oi.workload(0)
-    n = 2000896 + 3                                   # an array size of the paper's Table 1, plus a ragged tail
-    ha, hb, hc = oi.make_arrays(w, n=n)
-    a, b, c = (harness.GuardedArray(n, np.float64, off).upload(x) for x, off in zip((ha, hb, hc), (0, 1, 0)))
-    dt = opal.OPAL_F64
+    ha, hb, hc = (oi.uniform_array(w.seed, k, n, dtype, w.lo, w.hi, threads=16) for k in range(3))
+    a, b, c = (harness.GuardedArray(n, dtype, off).upload(x) for x, off in zip((ha, hb, hc), offsets))
+    dt = harness.opal_dtype(dtype)
+    tol = 1e-12 if np.dtype(dtype) == np.float64 else 1e-5
     ws_bytes = opal.opal_dot_workspace_bytes(n, dt)
     ws = torch.zeros(ws_bytes // 8, dtype=torch.float64, device="cuda:0")
     res = torch.zeros(1, dtype=torch.float64, device="cuda:0")
@@ -234,10 +234,10 @@ def test_graph_replay_matches_oracle(parity, harness):
     def check(what, want_dot):
         torch.cuda.synchronize()
         for name, d, h in (("a", a, ha), ("b", b, hb), ("c", c, hc)):
-            parity.assert_same_bits(d, h, "%s, array %s" % (what, name))
+            parity.assert_same_bits(d, h, "%s, array %s (n=%d %s)" % (what, name, n, np.dtype(dtype).name))
             assert d.guards_intact()
         got = float(res.item())
-        assert abs(got - want_dot) <= 1e-12 * abs(want_dot), (what, got, want_dot)
+        assert abs(got - want_dot) <= tol * abs(want_dot), (what, got, want_dot)
 
     side = torch.cuda.Stream()
     torch.cuda.synchronize()
@@ -251,14 +251,22 @@ def test_graph_replay_matches_oracle(parity, harness):
     torch.cuda.synchronize()
     check("after capture (capturing must not execute)", oracle.dot(ha, hb))
 
-    for k in range(5):
+    for k in range(replays):
         graph.replay()
         check("replay %d" % k, oracle_pass())
-        opal.opal_add(ea.ptr, eb.ptr, ec.ptr, 4099, dt, None)      # eager work between replays
+        opal.opal_add(ea.ptr, eb.ptr, ec.ptr, 4099, opal.OPAL_F64, None)      # eager work between replays
         torch.cuda.synchronize()
         assert (ec.download() == 5.0).all()
         res.fill_(float("nan"))
         torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("n,dtype", [(2000896 + 3, np.float64), (4000768, np.float64), (6000640, np.float64),
+                                     (2000896, np.float32), (6000640 + 1, np.float32)])
+def test_graph_replay_matches_oracle(parity, harness, n, dtype):
+    """The library neither allocates nor synchronises, so it can be captured into a HIP graph: the array
+    sizes of the paper's Table 1 (one with a ragged tail), both element types."""
+    graph_replay_check(parity, harness, n, dtype)
 
 
 # ------------------------------------------------------------------ special values
