@@ -4,7 +4,7 @@
 // put counter evidence behind the design choices of stream_kernels.hpp / pacing.hpp; the library
 // itself only contains the shapes that won.
 //
-//   shape_study [log2_n (default 28)] [launches per variant (default 9)] [group: all|ceilings|copy|triad|dot]
+//   shape_study [log2_n (default 28)] [launches per variant (default 9)] [group: all|ceilings|copy|triad|dot|lds]
 //
 // fp64 only.
 // Ceilings (kernels that only read or only write):
@@ -31,6 +31,15 @@
 //   dot_8_per_cu     tiled, eight per compute unit
 //   dot_tile         one tile per workgroup
 //   dot_paced        the library's shape for large arrays
+// LDS (group lds, not part of `all`; log2_n is ignored: 10240 tiles of 1024 vectors, 600 rounds, as the LDS bench):
+//   lds_stream       the library's LDS kernel: per round one 16-byte read and one 16-byte write per vector
+//   lds_stream_128, _512, _1024   the same with other workgroup sizes (the library uses 256)
+//   lds_mixed        the same rounds in this file's kernel, which also reads the clocks
+//   lds_read         the reads of a round only (same tile, same launch, same barrier per round)
+//   lds_write        the writes of a round only
+//   lds_write_b64, lds_write_b32   the same bytes written as 8-byte and 4-byte stores per lane
+//   lds_read2, lds_write2   twice the reads (writes) per round and barrier: both buffers
+//   clocks           what the two wave-readable counters count, and a chain of dependent fp32 adds per SIMD
 #include <algorithm>
 #include <cstdio>
 #include <cstdlib>
@@ -38,6 +47,7 @@
 #include <vector>
 
 #include "launch_shapes.hpp"
+#include "lds_kernel.hpp"
 #include "stream_kernels.hpp"
 
 using namespace opal;
@@ -155,6 +165,131 @@ __global__ __launch_bounds__(64) void paced_variant(double* out, const double* i
   paced_stream_body<double, OP, K, true>(out, in0, in1, s, p, pace);
 }
 
+// The rounds of lds_stream_kernel, whole (MODE 0), reads only (1) or writes only (2): same tile, same
+// workgroup, one barrier per round.  TWICE: the reads (writes) of a round go to both buffers, which
+// halves the barriers per byte (modes 1 and 2 only).  Thread 0 of every workgroup notes how far the shader clock
+// counter (s_memtime) and the constant-rate counter (s_memrealtime) advance over the rounds.
+template <int MODE, bool TWICE = false>
+__global__ __launch_bounds__(256) void lds_rounds(const double* __restrict__ in, double* __restrict__ out, double c,
+                                                  unsigned rep, unsigned long long* __restrict__ ticks) {
+  constexpr int BLOCK = 256, V = kLdsTileVectors / BLOCK;
+  __shared__ d2_t buf[2][kLdsTileVectors];
+  const unsigned t = threadIdx.x;
+  const size_t e0 = (size_t)blockIdx.x * kLdsTileVectors * 2;
+  const d2_t cv = (d2_t)(c);
+#pragma unroll
+  for (int u = 0; u < V; ++u) {
+    const d2_t v = load16<double, true, false>(in + e0 + (size_t)(t + u * BLOCK) * 2);
+    buf[0][t + u * BLOCK] = v;
+    buf[1][t + u * BLOCK] = v;
+  }
+  __syncthreads();
+  const unsigned long long m0 = __builtin_amdgcn_s_memtime(), r0 = __builtin_amdgcn_s_memrealtime();
+  unsigned cur = 0;
+  d2_t x[V];
+#pragma unroll
+  for (int u = 0; u < V; ++u) x[u] = cv;
+  for (unsigned r = 0; r < rep; ++r) {
+    if (MODE != 2) {
+      d2_t y[V];
+#pragma unroll
+      for (int u = 0; u < V; ++u) {
+        unsigned j = t + u * BLOCK + 1;
+        if (j == (unsigned)kLdsTileVectors) j = 0;
+        y[u] = buf[cur][j];
+      }
+#pragma unroll
+      for (int u = 0; u < V; ++u) x[u] = MODE == 0 ? y[u] + cv : x[u] + y[u];
+      if (MODE == 1 && TWICE) {
+#pragma unroll
+        for (int u = 0; u < V; ++u) {
+          unsigned j = t + u * BLOCK + 1;
+          if (j == (unsigned)kLdsTileVectors) j = 0;
+          y[u] = buf[cur ^ 1][j];
+        }
+#pragma unroll
+        for (int u = 0; u < V; ++u) x[u] += y[u];
+      }
+    } else {
+#pragma unroll
+      for (int u = 0; u < V; ++u) x[u] += cv;
+    }
+    if (MODE != 1) {
+#pragma unroll
+      for (int u = 0; u < V; ++u) buf[cur ^ 1][t + u * BLOCK] = x[u];
+      if (MODE == 2 && TWICE) {
+#pragma unroll
+        for (int u = 0; u < V; ++u) buf[cur][t + u * BLOCK] = x[u] + cv;
+      }
+    }
+    __syncthreads();
+    cur ^= 1;
+  }
+  const unsigned long long m1 = __builtin_amdgcn_s_memtime(), r1 = __builtin_amdgcn_s_memrealtime();
+  if (t == 0) {
+    ticks[2 * blockIdx.x] = m1 - m0;
+    ticks[2 * blockIdx.x + 1] = r1 - r0;
+  }
+#pragma unroll
+  for (int u = 0; u < V; ++u)
+    store16<double, false>(out + e0 + (size_t)(t + u * BLOCK) * 2, MODE == 1 ? x[u] : buf[cur][t + u * BLOCK]);
+}
+
+// Writes only, in pieces of W bytes per lane (8 or 4) at lane-consecutive addresses: the same 16 KiB per
+// round and barrier as lds_rounds<2>, as 2 or 4 times as many narrower stores.
+template <typename E>
+__global__ __launch_bounds__(256) void lds_write_narrow(const double* __restrict__ in, double* __restrict__ out, double c,
+                                                        unsigned rep, unsigned long long* __restrict__ ticks) {
+  constexpr int BLOCK = 256, N = kLdsTileVectors * 16 / sizeof(E), V = N / BLOCK;
+  __shared__ E buf[2][N];
+  const unsigned t = threadIdx.x;
+  const size_t e0 = (size_t)blockIdx.x * kLdsTileVectors * 2;
+  E x[V];
+#pragma unroll
+  for (int u = 0; u < V; ++u) {
+    x[u] = (E)in[e0 + (t + u * BLOCK) % (kLdsTileVectors * 2)];
+    buf[0][t + u * BLOCK] = x[u];
+    buf[1][t + u * BLOCK] = x[u];
+  }
+  __syncthreads();
+  const unsigned long long m0 = __builtin_amdgcn_s_memtime(), r0 = __builtin_amdgcn_s_memrealtime();
+  unsigned cur = 0;
+  for (unsigned r = 0; r < rep; ++r) {
+#pragma unroll
+    for (int u = 0; u < V; ++u) x[u] += (E)c;
+#pragma unroll
+    for (int u = 0; u < V; ++u) buf[cur ^ 1][t + u * BLOCK] = x[u];
+    __syncthreads();
+    cur ^= 1;
+  }
+  const unsigned long long m1 = __builtin_amdgcn_s_memtime(), r1 = __builtin_amdgcn_s_memrealtime();
+  if (t == 0) {
+    ticks[2 * blockIdx.x] = m1 - m0;
+    ticks[2 * blockIdx.x + 1] = r1 - r0;
+  }
+  double sum = 0;
+#pragma unroll
+  for (int u = 0; u < V; ++u) sum += (double)buf[cur][t + u * BLOCK];
+  out[e0 + t] = sum;
+}
+
+// One wavefront per SIMD (256-thread workgroups, one per compute unit) runs `ops` dependent fp32 adds.
+__global__ __launch_bounds__(256) void add_chain(float* __restrict__ out, float c, unsigned ops,
+                                                 unsigned long long* __restrict__ ticks) {
+  float x = (float)threadIdx.x;
+  const unsigned long long m0 = __builtin_amdgcn_s_memtime(), r0 = __builtin_amdgcn_s_memrealtime();
+  for (unsigned i = 0; i < ops; i += 16) {
+#pragma unroll
+    for (int k = 0; k < 16; ++k) asm volatile("v_add_f32 %0, %0, %1" : "+v"(x) : "v"(c));
+  }
+  const unsigned long long m1 = __builtin_amdgcn_s_memtime(), r1 = __builtin_amdgcn_s_memrealtime();
+  if (threadIdx.x == 0) {
+    ticks[2 * blockIdx.x] = m1 - m0;
+    ticks[2 * blockIdx.x + 1] = r1 - r0;
+  }
+  out[(size_t)blockIdx.x * 256 + threadIdx.x] = x;
+}
+
 __global__ void fill(double* p, size_t n) {
   for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
     p[i] = 0.5 + (double)(i & 1023) * 9.765625e-4;
@@ -175,14 +310,113 @@ static Pace make_pace(const PacedShape& sh, unsigned streams, bool timetable, bo
   return pace;
 }
 
+// LDS rates in bytes per clock per compute unit, against the two clocks a wave can read.
+static int lds_study(int launches) {
+  const unsigned tiles = 10240, rep = 600;
+  const size_t n = (size_t)tiles * kLdsTileVectors * 2;
+  int cus = 0, khz = 0;
+  CHECK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, 0));
+  CHECK(hipDeviceGetAttribute(&khz, hipDeviceAttributeClockRate, 0));
+  double *in = nullptr, *out = nullptr;
+  unsigned long long* ticks = nullptr;
+  CHECK(hipMalloc(&in, n * 8));
+  CHECK(hipMalloc(&out, n * 8));
+  CHECK(hipMalloc(&ticks, (size_t)tiles * 16));
+  study::fill<<<4096, 256>>>(in, n);
+  CHECK(hipDeviceSynchronize());
+  hipEvent_t e0, e1;
+  CHECK(hipEventCreate(&e0));
+  CHECK(hipEventCreate(&e1));
+  std::vector<unsigned long long> host((size_t)tiles * 2);
+  printf("LDS: %u tiles of %d vectors, %u rounds, %d compute units, reported clock %.0f MHz, %d launches per variant\n",
+         tiles, kLdsTileVectors, rep, cus, khz / 1e3, launches);
+  printf("%-16s %10s %10s %12s %14s %16s\n", "variant", "median us", "LDS GB/s", "B/clk/CU at", "s_memtime per", "B per s_memtime");
+  printf("%-16s %10s %10s %12s %14s %16s\n", "", "", "", "reported clk", "s_memrealtime", "tick per CU");
+  auto run = [&](const char* name, double bytes_per_vector_round, unsigned groups, auto&& launch) {
+    std::vector<float> ms;
+    launch();
+    for (int i = 0; i < launches; ++i) {
+      CHECK(hipEventRecord(e0, 0));
+      launch();
+      CHECK(hipEventRecord(e1, 0));
+      CHECK(hipEventSynchronize(e1));
+      float t;
+      CHECK(hipEventElapsedTime(&t, e0, e1));
+      ms.push_back(t);
+    }
+    CHECK(hipGetLastError());
+    std::sort(ms.begin(), ms.end());
+    const double us = ms[ms.size() / 2] * 1e3;
+    const double total = bytes_per_vector_round * tiles * (double)kLdsTileVectors * rep;
+    double ratio = 0, per_tick = 0;
+    if (groups) {
+      CHECK(hipMemcpy(host.data(), ticks, (size_t)groups * 16, hipMemcpyDeviceToHost));
+      double m = 0, r = 0;
+      for (unsigned g = 0; g < groups; ++g) {
+        m += (double)host[2 * g];
+        r += (double)host[2 * g + 1];
+      }
+      ratio = m / r;
+      // s_memtime ticks of the whole launch = ratio * (100 ticks per us) * us
+      per_tick = total / (ratio * 100.0 * us) / cus;
+    }
+    if (groups)
+      printf("%-16s %10.1f %10.0f %12.1f %14.3f %16.1f\n", name, us, total / us / 1e3, total / us / 1e3 / (khz / 1e6) / cus,
+             ratio, per_tick);
+    else
+      printf("%-16s %10.1f %10.0f %12.1f %14s %16s\n", name, us, total / us / 1e3, total / us / 1e3 / (khz / 1e6) / cus, "-", "-");
+    fflush(stdout);
+  };
+  run("lds_stream", 32.0, 0, [&] { lds_stream_kernel<double, 256><<<tiles, 256>>>(in, out, 0.5, rep); });
+  run("lds_stream_128", 32.0, 0, [&] { lds_stream_kernel<double, 128><<<tiles, 128>>>(in, out, 0.5, rep); });
+  run("lds_stream_512", 32.0, 0, [&] { lds_stream_kernel<double, 512><<<tiles, 512>>>(in, out, 0.5, rep); });
+  run("lds_stream_1024", 32.0, 0, [&] { lds_stream_kernel<double, 1024><<<tiles, 1024>>>(in, out, 0.5, rep); });
+  run("lds_mixed", 32.0, tiles, [&] { study::lds_rounds<0><<<tiles, 256>>>(in, out, 0.5, rep, ticks); });
+  run("lds_read", 16.0, tiles, [&] { study::lds_rounds<1><<<tiles, 256>>>(in, out, 0.5, rep, ticks); });
+  run("lds_write", 16.0, tiles, [&] { study::lds_rounds<2><<<tiles, 256>>>(in, out, 0.5, rep, ticks); });
+  run("lds_write_b64", 16.0, tiles, [&] { study::lds_write_narrow<double><<<tiles, 256>>>(in, out, 0.5, rep, ticks); });
+  run("lds_write_b32", 16.0, tiles, [&] { study::lds_write_narrow<float><<<tiles, 256>>>(in, out, 0.5, rep, ticks); });
+  run("lds_read2", 32.0, tiles, [&] { study::lds_rounds<1, true><<<tiles, 256>>>(in, out, 0.5, rep, ticks); });
+  run("lds_write2", 32.0, tiles, [&] { study::lds_rounds<2, true><<<tiles, 256>>>(in, out, 0.5, rep, ticks); });
+  // clocks: `ops` dependent fp32 adds on one wavefront per SIMD
+  const unsigned ops = 1u << 20;
+  float* fout = nullptr;
+  CHECK(hipMalloc(&fout, (size_t)cus * 256 * 4));
+  std::vector<float> ms;
+  for (int i = 0; i < launches + 1; ++i) {
+    CHECK(hipEventRecord(e0, 0));
+    study::add_chain<<<cus, 256>>>(fout, 1.0f, ops, ticks);
+    CHECK(hipEventRecord(e1, 0));
+    CHECK(hipEventSynchronize(e1));
+    float t;
+    CHECK(hipEventElapsedTime(&t, e0, e1));
+    if (i) ms.push_back(t);
+  }
+  CHECK(hipGetLastError());
+  std::sort(ms.begin(), ms.end());
+  CHECK(hipMemcpy(host.data(), ticks, (size_t)cus * 16, hipMemcpyDeviceToHost));
+  double m = 0, r = 0;
+  for (int g = 0; g < cus; ++g) {
+    m += (double)host[2 * g];
+    r += (double)host[2 * g + 1];
+  }
+  printf("clocks: a chain of %u dependent fp32 adds (one wavefront per SIMD) takes %.1f us by events, %.0f s_memrealtime ticks "
+         "and %.0f s_memtime ticks per wavefront: %.3f s_memtime ticks per add, %.3f s_memtime per s_memrealtime tick "
+         "(s_memrealtime counts at 100 MHz)\n",
+         ops, ms[ms.size() / 2] * 1e3, r / cus, m / cus, m / cus / ops, m / r);
+  CHECK(hipDeviceSynchronize());
+  return 0;
+}
+
 int main(int argc, char** argv) {
   const int lg = argc > 1 ? atoi(argv[1]) : 28;
   const int launches = argc > 2 ? atoi(argv[2]) : 9;
   const char* group = argc > 3 ? argv[3] : "all";
   if (lg < 24 || lg > 30 || launches < 1) {
-    fprintf(stderr, "usage: shape_study [log2_n 24..30] [launches >= 1] [all|ceilings|copy|triad|dot]\n");
+    fprintf(stderr, "usage: shape_study [log2_n 24..30] [launches >= 1] [all|ceilings|copy|triad|dot|lds]\n");
     return 2;
   }
+  if (!strcmp(group, "lds")) return lds_study(launches);
   auto want = [&](const char* g) { return !strcmp(group, "all") || !strcmp(group, g); };
   const size_t n = (size_t)1 << lg, nvec = n / 2, bytes = n * 8, skew = 1024;
   int cus = 0;

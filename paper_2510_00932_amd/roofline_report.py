@@ -16,7 +16,10 @@ Any subset of counters may be present; lines whose counters are missing are left
 Peaks (MI355X): HBM 8.0 TB/s and vector fp64 78.6 / fp32 157.3 TFLOP/s are published; the cache
 levels are derived from unit counts, widths per clock and the 2.4 GHz peak clock: L2 = 8 XCDs x 16
 channels x 128 B/clk = 39.3 TB/s; L1 (vector cache to L2 and to the compute unit) = 256 compute
-units x 64 B/clk = 39.3 TB/s; LDS = 256 compute units x 128 B/clk = 78.6 TB/s.
+units x 64 B/clk = 39.3 TB/s.  The LDS has a published figure for reads only (256 B/clk per compute
+unit on CDNA 4, twice the 128 B/clk of CDNA 3, which was one figure for reads and writes); its lines are
+given in bytes per clock per compute unit against that read figure and against the rates that read-only
+and write-only variants of the same kernel reach (shape_study, group lds).
 """
 import argparse
 import csv
@@ -29,7 +32,9 @@ VALU_PEAK = {"f64": 78.6e12, "f32": 157.3e12}
 CLOCK_HZ = 2.4e9
 L2_PEAK = 8 * 16 * 128 * CLOCK_HZ       # bytes per second
 L1_PEAK = 256 * 64 * CLOCK_HZ
-LDS_PEAK = 256 * 128 * CLOCK_HZ
+LDS_READ_PEAK_B_PER_CLK_CU = 256.0                       # published, CDNA 4, reads
+# measured with shape_study's read-only and write-only variants of the LDS kernel (same tile, same launch)
+LDS_MEASURED_B_PER_CLK_CU = {"read": 209.0, "write": 77.0}
 CAL_KERNEL = "__amd_rocclr_copyBuffer"
 CAL_BYTES = 1 << 30
 
@@ -201,29 +206,56 @@ def analyse(root, n, dtype):
     return results, lines
 
 
+def lds_composed_rate(read=None, write=None):
+    """Bytes per clock per compute unit of a round that reads and writes the same number of bytes when reads run at
+    `read` and writes at `write` bytes per clock and share one pipe (the times add)."""
+    read = LDS_MEASURED_B_PER_CLK_CU["read"] if read is None else read
+    write = LDS_MEASURED_B_PER_CLK_CU["write"] if write is None else write
+    return 2.0 / (1.0 / read + 1.0 / write)
+
+
 def analyse_lds(root, n, dtype, rep):
-    """The LDS microkernel: observed LDS bandwidth (32 bytes per 16-byte vector per round, from the definition, and
-    from the LDS load/store bandwidth counters where present) against the LDS peak."""
+    """The LDS microkernel: observed LDS bandwidth (32 bytes per 16-byte vector per round, from the definition) per
+    compute unit and clock, against the published read rate and the measured read-only and write-only rates."""
     stats = read_kernel_stats(root)
     counters = read_counters(root)
     width = 8 if dtype == "f64" else 4
-    st = pick(stats, LDS_KERNEL + (("double" if dtype == "f64" else "float"),))
+    needle = LDS_KERNEL + (("double" if dtype == "f64" else "float"),)
+    st = pick(stats, needle)
     if not st:
         return []
     t = st[1] * 1e-9
     lds_bytes = 32.0 * (n * width / 16) * rep
+    rate = lds_bytes / t / 256 / CLOCK_HZ                      # bytes per clock per compute unit, read + written
+    composed = lds_composed_rate()
     lines = ["", "lds_stream (n = %d %s, rep = %d)" % (n, dtype, rep),
-             "  time per launch %.1f us; LDS traffic by definition %.3e bytes -> %.0f GB/s = %.1f %% of the %.1f TB/s LDS peak"
-             % (t * 1e6, lds_bytes, lds_bytes / t / 1e9, 100 * lds_bytes / t / LDS_PEAK, LDS_PEAK / 1e12),
-             "  per compute unit and clock at 2.4 GHz: %.1f bytes (%.1f read + %.1f written)"
-             % (lds_bytes / t / 256 / CLOCK_HZ, lds_bytes / t / 256 / CLOCK_HZ / 2, lds_bytes / t / 256 / CLOCK_HZ / 2)]
-    needle = LDS_KERNEL + (("double" if dtype == "f64" else "float"),)
+             "  time per launch %.1f us; LDS traffic by definition %.3e bytes -> %.0f GB/s"
+             % (t * 1e6, lds_bytes, lds_bytes / t / 1e9),
+             "  per compute unit and clock at 2.4 GHz: %.1f bytes (%.1f read + %.1f written)" % (rate, rate / 2, rate / 2),
+             "  reads alone: %.1f %% of the published %.0f B/clk/CU read rate" % (100 * rate / 2 / LDS_READ_PEAK_B_PER_CLK_CU,
+                                                                              LDS_READ_PEAK_B_PER_CLK_CU),
+             "  measured ceilings of the same kernel: read-only %.0f, write-only %.0f B/clk/CU; reads and writes share one "
+             "pipe, so a round at those rates moves %.1f B/clk/CU: the kernel is at %.0f %% of that"
+             % (LDS_MEASURED_B_PER_CLK_CU["read"], LDS_MEASURED_B_PER_CLK_CU["write"], composed, 100 * rate / composed)]
     conf, idx = pick(counters.get("SQ_LDS_BANK_CONFLICT", {}), needle), pick(counters.get("SQ_LDS_IDX_ACTIVE", {}), needle)
+    insts = pick(counters.get("SQ_INSTS_LDS", {}), needle)
     if conf is not None and idx:
         lines.append("  LDS bank conflicts: %.2f %% of LDS-active cycles" % (100 * conf / idx))
-    frac = lds_bytes / t / LDS_PEAK
-    lines.append("  => LDS is %s (%.0f %% of peak); HBM carries only one read and one write of the tile (%.3f %% of its peak)"
-                 % ("the binding component" if frac >= 0.8 else "under-used", 100 * frac,
+    if idx:
+        lines.append("  LDS index unit active %.0f %% of the kernel's cycles%s"
+                     % (100 * idx / (256 * t * CLOCK_HZ),
+                        (", %.1f cycles per LDS instruction (a 16-byte read and a 16-byte write per lane in turn)" % (idx / insts))
+                        if insts else ""))
+    frac = rate / composed
+    lines.append("  => the LDS %s; its read path is under-used (%.0f %% of the published read rate) because the writes of "
+                 "every round hold the pipe for %.0f %% of the time; HBM carries only one read and one write of the tile "
+                 "(%.3f %% of its peak)"
+                 % ("write rate is the binding component (the kernel runs at what the measured read-only and write-only "
+                    "rates compose to)" if frac >= 0.9 else
+                    "is under-used (%.0f %% of what the measured read-only and write-only rates compose to)" % (100 * frac),
+                    100 * rate / 2 / LDS_READ_PEAK_B_PER_CLK_CU,
+                    100 * (1.0 / LDS_MEASURED_B_PER_CLK_CU["write"]) /
+                    (1.0 / LDS_MEASURED_B_PER_CLK_CU["write"] + 1.0 / LDS_MEASURED_B_PER_CLK_CU["read"]),
                     100 * 2 * n * width / t / HBM_PEAK))
     return lines
 
