@@ -228,6 +228,69 @@ def call_overhead(args):
                       "unit": "us", "calls": calls, "results": results}))
 
 
+def placement_scan(args):
+    """How the two launch shapes of the elementwise kernels depend on where the three arrays lie relative to each
+    other.  The arrays (2^28 fp64 by default, random values: zero-filled arrays hide the effect) are carved out of
+    one allocation at base + k * (array bytes + skew), k = 0, 1, 2, for a list of skews; copy (a -> c), add and triad
+    are timed with the paced shapes on and off (average of `--steps` launches each, percent of the HBM peak).
+    Prints one JSON line."""
+    import torch
+
+    import opal_inputs as oi
+    import paper_2510_00932_amd as opal
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the kernels have no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    opal.load()
+    wl = oi.workload(args.workload)
+    n = args.n if args.n is not None else wl.n
+    dt, tdt, item = (opal.OPAL_F64, torch.float64, 8) if wl.dtype == "f64" else (opal.OPAL_F32, torch.float32, 4)
+    skews = [int(v) for v in args.placement_scan.split(",")]
+    if any(v < 0 or v % 256 for v in skews):
+        print("bench.py: skews must be non-negative multiples of 256", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    nbytes = n * item
+    pool = torch.empty(3 * (nbytes + max(skews)) + 256, dtype=torch.uint8, device=dev)
+    src = [torch.from_numpy(x).to(dev) for x in oi.make_arrays(wl, n=n, threads=min(16, os.cpu_count() or 1))]
+    stream = torch.cuda.Stream()
+    steps = max(3, min(args.steps, 20))
+    rows = []
+    mode0 = opal.opal_get_pacing()
+    try:
+        for skew in skews:
+            pitch = nbytes + skew
+            a, b, c = (pool[k * pitch:k * pitch + nbytes].view(tdt) for k in range(3))
+            for d, h in zip((a, b, c), src):
+                d.copy_(h)
+            torch.cuda.synchronize()
+            pa, pb, pc = a.data_ptr(), b.data_ptr(), c.data_ptr()
+            row = {"skew_bytes": skew}
+            for mode, label in ((1, "paced"), (0, "ordered")):
+                opal.opal_set_pacing(mode)
+                for name, launch, moved in (("copy", lambda: opal.opal_copy(pa, pc, n, dt, stream), 2 * nbytes),
+                                            ("add", lambda: opal.opal_add(pa, pb, pc, n, dt, stream), 3 * nbytes),
+                                            ("triad", lambda: opal.opal_triad(pa, pb, pc, wl.s, n, dt, stream), 3 * nbytes)):
+                    launch()
+                    launch()
+                    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+                    for e0, e1 in ev:
+                        e0.record(stream)
+                        launch()
+                        e1.record(stream)
+                    stream.synchronize()
+                    avg_ms = sum(e0.elapsed_time(e1) for e0, e1 in ev) / steps
+                    row["%s_%s" % (name, label)] = round(100 * moved / (avg_ms * 1e-3) / (HBM_PEAK_GBS * 1e9), 1)
+            rows.append(row)
+            print("bench.py: skew %d done" % skew, file=sys.stderr, flush=True)
+    finally:
+        opal.opal_set_pacing(mode0)
+    print(json.dumps({"metric": "percent of the HBM peak against the relative placement of the arrays, 1 GPU", "unit": "%",
+                      "config": {"workload": wl.name, "n": n}, "dtype": wl.dtype, "data": "synthetic",
+                      "launches_per_figure": steps, "results": rows}))
+
+
 def lds_bench(args):
     """LDS-streaming microkernel (the analogue of the shared-memory benchmark subject of the paper's
     Table 1, rep = 300..1500, default 600): achieved LDS bandwidth = 32 bytes per 16-byte vector per
@@ -318,6 +381,9 @@ def main():
     ap.add_argument("--paper-shapes", action="store_true",
                     help="instead of the roofline benchmark, time the paper's own (small, cache-resident) array "
                          "sizes and repetition counts issued eagerly and through HIP graphs")
+    ap.add_argument("--placement-scan", default=None, metavar="SKEW[,SKEW...]",
+                    help="instead of the roofline benchmark, time copy, add and triad with the paced shapes on and off "
+                         "for each of these skews (bytes between consecutive arrays beyond the array size)")
     ap.add_argument("--lds-rep", type=int, default=0,
                     help="with --lds: time this repetition count only (default: the paper's five, 300..1500)")
     ap.add_argument("--call-overhead", action="store_true",
@@ -342,6 +408,9 @@ def main():
         return
     if args.call_overhead:
         call_overhead(args)
+        return
+    if args.placement_scan:
+        placement_scan(args)
         return
 
     import numpy as np
