@@ -37,9 +37,19 @@ constexpr unsigned kDotMaxGroups = 8192;   // 64 KiB of fp64 partials at most
 constexpr unsigned kFinalBlock = 256;
 
 // Paced shapes.  Rates are what the timetable asks of the memory system, in bytes per
-// microsecond (= MB/s / 1e... i.e. 7.0e6 is 7.0 TB/s): slightly more than HBM sustains, so the
-// timetable, not the queues, orders the traffic, and the feedback of pacing.hpp absorbs the
-// difference.  Measured optimum on MI355X (8 TB/s HBM3E, 256 compute units, 100 MHz counter).
+// microsecond (7.0e6 is 7.0 TB/s): slightly more than HBM sustains, so the timetable, not the
+// queues, orders the traffic, and the feedback of pacing.hpp absorbs the difference.  Measured
+// optimum on MI355X (8 TB/s HBM3E, 256 compute units, 100 MHz counter).
+//
+// Placement.  Both elementwise shapes hand XCD x the 1 KiB runs whose index is x modulo 8, so an
+// XCD keeps reaching the same memory channels of an array.  For kernels with two inputs the
+// distance between the arrays then matters: the paced shape is at its best (86-88 % of the HBM
+// peak at 2 GiB per array) when the arrays are congruent modulo 16 KiB to within 3 KiB and
+// modulo 4 MiB to within 256 KiB, and at 81.5-83.5 % otherwise; the index-ordered shape behaves
+// the other way round (84-85 % where the arrays differ by 4-12 KiB modulo 16 KiB, 81-83 % where
+// they are congruent).  Over a scan of placements the paced shapes are ahead on average for
+// every kernel and never behind the index-ordered worst case, so the choice of shape does not
+// look at the pointers.
 struct PacedShape {
   unsigned waves;          // persistent wavefronts (8 or 4 per compute unit)
   unsigned k;              // 1 KiB runs per wavefront per burst
