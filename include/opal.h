@@ -117,12 +117,13 @@ int opal_dot(const void* a, const void* b, size_t n, int dtype,
 size_t opal_dot_static_scratch_bytes(void);
 int opal_dot_static(const void* a, const void* b, size_t n, int dtype, double* result, void* stream);
 
-/* Launch shapes for arrays far beyond the caches ("paced" shapes).  For arrays of at least
- * 192 MiB on an MI355X the five kernels run as persistent wavefronts that issue their loads and
- * stores in bursts on a common timetable read off the chip-wide constant-rate counter, so that
- * HBM sees one stream and one direction at a time (about 2 % more bytes per second for the
- * elementwise kernels, 4 % for Dot, than workgroups handed out in index order; the switch is at
- * 768 MiB per array for Copy and Mul, 512 MiB for Add and Triad, 384 MiB for Dot).  Results are the
+/* Launch shapes for arrays far beyond the caches ("paced" shapes).  For large arrays on an
+ * MI355X (from 768 MiB per array for Copy and Mul, 512 MiB for Add and Triad, 384 MiB for Dot)
+ * the five kernels run as persistent wavefronts that issue their loads and stores in bursts on a
+ * common timetable read off the chip-wide constant-rate counter, so that HBM sees one stream and
+ * one direction at a time (2-3 % more bytes per second for the elementwise kernels, 3-4 % for
+ * Dot, than workgroups handed out in index order; for Add and Triad the gain depends on how the
+ * two input arrays lie relative to each other, see csrc/launch_shapes.hpp).  Results are the
  * same bits either way.  The timetable keeps a few device words of feedback inside the library's
  * device image (one copy per GPU); calls that overlap on one GPU share them, which can only cost
  * speed.  opal_set_pacing(0) switches to index-ordered workgroups for every size, 1 (the
