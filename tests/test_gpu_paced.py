@@ -135,6 +135,54 @@ def test_paced_kernels_replay_from_a_hip_graph(parity, pacing):
     graph_replay_check(parity, gpu_harness, _sizes(np.float64)[0], np.float64, offsets=(1, 1, 1), replays=3)
 
 
+def test_overlapping_paced_calls_on_two_streams(pacing):
+    """Paced kernels on one GPU share the timetable's feedback words, so two that overlap may read each other's
+    lateness reports: that may cost time, never a result bit.  Two independent chains on two streams, launched
+    alternately without synchronising in between, each compared with the oracle."""
+    import oracle
+    n = _sizes(np.float64)[0]
+    w = oi.workload(4)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    host, dev, res, ws = [], [], [], []
+    need = opal.opal_dot_workspace_bytes(n, opal.OPAL_F64)
+    for j in range(2):
+        h = [oi.uniform_array(w.seed + j, k, n, np.float64, w.lo, w.hi, threads=16) for k in range(3)]
+        host.append(h)
+        dev.append([torch.from_numpy(x).cuda() for x in h])
+        res.append(torch.full((1,), float("nan"), dtype=torch.float64, device="cuda:0"))
+        ws.append(torch.empty(need // 8, dtype=torch.float64, device="cuda:0"))
+    torch.cuda.synchronize()
+    dt = opal.OPAL_F64
+    for rep in range(3):
+        for call in range(5):
+            for j in range(2):
+                a, b, c = dev[j]
+                st = streams[j]
+                if call == 0:
+                    opal.opal_copy(a, c, n, dt, st)
+                elif call == 1:
+                    opal.opal_scale(b, c, w.s, n, dt, st)
+                elif call == 2:
+                    opal.opal_add(a, b, c, n, dt, st)
+                elif call == 3:
+                    opal.opal_triad(a, b, c, w.s, n, dt, st)
+                else:
+                    opal.opal_dot(a, b, n, dt, ws[j], need, res[j].data_ptr(), st)
+    torch.cuda.synchronize()
+    for j in range(2):
+        ha, hb, hc = host[j]
+        for rep in range(3):
+            oracle.copy(ha, hc)
+            oracle.scale(hb, hc, w.s)
+            oracle.add(ha, hb, hc)
+            oracle.triad(ha, hb, hc, w.s)
+        ref = oracle.dot(ha, hb)
+        for name, d, h in zip("abc", dev[j], (ha, hb, hc)):
+            assert np.array_equal(d.cpu().numpy().view(np.uint64), h.view(np.uint64)), "chain %d, array %s" % (j, name)
+        got = float(res[j].item())
+        assert abs(got - ref) <= 1e-12 * abs(ref), (j, got, ref)
+
+
 def test_pacing_configure_rejects_bad_values():
     for args in ((3, 7.0, 0.5, 0.0, 0.0, 100, 1), (-1, 7.0, 0.5, 0.0, 0.0, 100, 1), (0, 0.0, 0.5, 0.0, 0.0, 100, 1),
                  (0, 1e9, 0.5, 0.0, 0.0, 100, 1), (0, 7.0, 1.0, 0.0, 0.0, 100, 1), (0, 7.0, -0.1, 0.0, 0.0, 100, 1),
