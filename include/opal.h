@@ -143,7 +143,9 @@ int opal_get_pacing(void);
  * wavefront has to be before the timetable is pushed back, whether lateness is fed back at
  * all, and which bit of the workgroup index splits the wavefronts into the two sets (0..8; 3 puts
  * whole compute units into one set).  Defaults are the measured optimum on MI355X; a timetable that asks too much degrades to
- * unordered traffic, it never affects results.  OPAL_ERR_SIZE for a value out of range. */
+ * unordered traffic, it never affects results.  OPAL_ERR_SIZE for a value out of range.
+ * Like opal_set_pacing it changes process-wide state that every launch reads: call it while no
+ * other thread is inside the library. */
 int opal_pacing_configure(int kind, double terabytes_per_second, double store_at, double second_input_at,
                           double gap, unsigned tolerance_ticks, int feedback, unsigned set_bit);
 

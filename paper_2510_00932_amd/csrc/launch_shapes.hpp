@@ -66,7 +66,7 @@ constexpr unsigned kPacedCUs = 256;             // the timetable is for this chi
 constexpr int kPacedK1 = 8;                     // one-input kernels (copy, scale): K
 constexpr int kPacedK2 = 4;                     // two-input kernels (add, triad): K
 constexpr int kPacedKDot = 8;
-constexpr PacedShape kPacedOneInput = {2048, kPacedK1, 3, 7.05e6, 0.75, 0.0, 0.02, 400, (size_t)768 << 20, true};
+constexpr PacedShape kPacedOneInput = {2048, kPacedK1, 3, 7.10e6, 0.75, 0.0, 0.035, 400, (size_t)768 << 20, true};
 constexpr PacedShape kPacedTwoInputs = {2048, kPacedK2, 3, 7.10e6, 0.0, 0.0, 0.03, 400, (size_t)512 << 20, true};
 constexpr PacedShape kPacedDot = {1024, kPacedKDot, 3, 7.60e6, 0.0, 0.25, 0.0, 0, (size_t)384 << 20, false};
 

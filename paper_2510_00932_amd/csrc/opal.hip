@@ -9,6 +9,7 @@
 #include <atomic>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 
 #include "../../include/opal.h"
 #include "launch_plan.hpp"
@@ -83,8 +84,12 @@ const DeviceInfo* device_info() {
     overflow = d;
     return &overflow;
   }
-  info[dev] = d;   // two threads may both get here: they write the same values
-  ready[dev].store(1, std::memory_order_release);
+  static std::mutex fill;
+  std::lock_guard<std::mutex> lock(fill);
+  if (!ready[dev].load(std::memory_order_acquire)) {
+    info[dev] = d;
+    ready[dev].store(1, std::memory_order_release);
+  }
   return &info[dev];
 }
 
