@@ -527,6 +527,7 @@ def main():
             "GBps_avg": round(nbytes / avg / 1e6, 1), "GBps_best": round(nbytes / mn / 1e6, 1),
             "GBps_median": round(nbytes / med / 1e6, 1),
             "frac_of_peak_avg": round(nbytes / avg / 1e6 / HBM_PEAK_GBS, 4),
+            "launches_over_1.03x_median": sum(1 for t in ms if t > 1.03 * med),
         }
     # The kernel with the largest share of the step; add and triad move the same bytes and tie to
     # within noise, so a tie (1 %) goes to triad, which also does the most arithmetic.

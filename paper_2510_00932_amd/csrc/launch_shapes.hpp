@@ -62,6 +62,10 @@ struct PacedShape {
   size_t min_bytes;        // smallest array (bytes) the shape is used for
   bool feedback;
 };
+// Rates and gaps were settled by interleaved comparisons (the settings alternate from launch to
+// launch inside one process, 120-150 launches each, chain of the five kernels at 2 GiB per array):
+// what differs between settings is mostly how many launches have one XCD fall behind the
+// timetable (such a launch is 5-20 % slow), not the speed of a good launch.
 constexpr unsigned kPacedCUs = 256;             // the timetable is for this chip only
 constexpr int kPacedK1 = 8;                     // one-input kernels (copy, scale): K
 constexpr int kPacedK2 = 4;                     // two-input kernels (add, triad): K

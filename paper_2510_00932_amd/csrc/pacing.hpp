@@ -75,8 +75,9 @@ struct PaceState {
 __device__ __forceinline__ PaceState pace_begin(const Pace& p, unsigned set) {
   PaceState st;
   const uint64_t t = pace_clock64();
-  const uint32_t t32 = (uint32_t)t;
-  st.next = (t32 / p.period + 1u) * p.period + set * (p.period / 2u);
+  // Period boundaries are counted on the 64-bit counter, so that wavefronts starting on either
+  // side of a wrap of its low 32 bits still agree on them.
+  st.next = (uint32_t)((t / p.period + 1u) * p.period) + set * (p.period / 2u);
   st.stretch = 0;
   st.stamp = (t >> 9) & (((uint64_t)1 << 44) - 1);
   return st;
