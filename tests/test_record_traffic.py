@@ -6,11 +6,14 @@ import shutil
 import subprocess
 import sys
 
+import pytest
+
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-SAMPLE = os.path.join(ROOT, "tests", "golden", "rocprof_n2p28_f64")
+SAMPLES = [os.path.join(ROOT, "tests", "golden", d) for d in ("rocprof_n2p28_f64", "rocprof_n2p28_f64_paced")]
 
 
-def test_traffic_record_from_the_sample(tmp_path, monkeypatch):
+@pytest.mark.parametrize("SAMPLE", SAMPLES, ids=["ordered", "paced"])
+def test_traffic_record_from_the_sample(tmp_path, monkeypatch, SAMPLE):
     sys.path.insert(0, ROOT)
     from paper_2510_00932_amd import record_traffic as rt
     for sub in ("f", "w"):

@@ -5,12 +5,19 @@ import pytest
 
 from paper_2510_00932_amd import roofline_report as rr
 
-SAMPLE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "rocprof_n2p28_f64")
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+SAMPLE = os.path.join(GOLDEN, "rocprof_n2p28_f64")                 # index-ordered shapes
+SAMPLE_PACED = os.path.join(GOLDEN, "rocprof_n2p28_f64_paced")     # paced shapes (the default at this size)
+
+
+@pytest.fixture(scope="module", params=[SAMPLE, SAMPLE_PACED], ids=["ordered", "paced"])
+def sample(request):
+    return request.param
 
 
 @pytest.fixture(scope="module")
-def report():
-    return rr.analyse(SAMPLE, 1 << 28, "f64")
+def report(sample):
+    return rr.analyse(sample, 1 << 28, "f64")
 
 
 def test_every_kernel_is_reported(report):
@@ -19,7 +26,7 @@ def test_every_kernel_is_reported(report):
     assert any(line.startswith("Roofline position") for line in lines)
 
 
-def test_bandwidth_is_bytes_over_time(report):
+def test_bandwidth_is_bytes_over_time(report, sample):
     results = dict(report[0])
     n = 1 << 28
     for name, words in (("copy", 2), ("scale", 2), ("add", 3), ("triad", 3), ("dot", 2)):
@@ -29,15 +36,15 @@ def test_bandwidth_is_bytes_over_time(report):
         assert m["hbm_frac"] == pytest.approx(m["hbm_bytes_per_s"] / 8.0e12)
         assert 0.5 < m["hbm_frac"] < 1.0
     # dot's time is both passes together
-    stats = rr.read_kernel_stats(SAMPLE)
-    t1 = rr.pick(stats, "dot_partial_kernel")[1]
+    stats = rr.read_kernel_stats(sample)
+    t1 = rr.pick(stats, "dot_partial_kernel" if sample == SAMPLE else "paced_dot_kernel")[1]
     t2 = rr.pick(stats, "dot_final_kernel")[1]
     assert results["dot"]["seconds"] == pytest.approx((t1 + t2) * 1e-9)
 
 
-def test_counters_are_calibrated_against_the_known_copy(report):
+def test_counters_are_calibrated_against_the_known_copy(report, sample):
     results = dict(report[0])
-    counters = rr.read_counters(SAMPLE)
+    counters = rr.read_counters(sample)
     cal = rr.pick(counters["FETCH_SIZE"], rr.CAL_KERNEL)
     f = rr.pick(counters["FETCH_SIZE"], "(opal::Op)3")
     w = rr.pick(counters["WRITE_SIZE"], "(opal::Op)3")
