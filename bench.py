@@ -232,8 +232,7 @@ def placement_scan(args):
     """How the two launch shapes of the elementwise kernels depend on where the three arrays lie relative to each
     other.  The arrays (2^28 fp64 by default, random values: zero-filled arrays hide the effect) are carved out of
     one allocation at base + k * (array bytes + skew), k = 0, 1, 2, for a list of skews; copy (a -> c), add and triad
-    are timed with the paced shapes forced, switched off, and left to the library's own choice (which looks at where
-    the two inputs lie: opal_input_placement); average of `--steps` launches each, percent of the HBM peak.
+    are timed with the paced shapes on and off (average of `--steps` launches each, percent of the HBM peak).
     Prints one JSON line."""
     import torch
 
@@ -267,11 +266,8 @@ def placement_scan(args):
                 d.copy_(h)
             torch.cuda.synchronize()
             pa, pb, pc = a.data_ptr(), b.data_ptr(), c.data_ptr()
-            row = {"skew_bytes": skew,
-                   # share (in 64ths) of the runs whose inputs, add (a, b) / triad (b, c), fall into different channel classes
-                   "add_input_mismatch": opal.opal_input_placement(pa, pb, n, dt),
-                   "triad_input_mismatch": opal.opal_input_placement(pb, pc, n, dt)}
-            for mode, label in ((2, "paced"), (0, "ordered"), (1, "chosen")):
+            row = {"skew_bytes": skew}
+            for mode, label in ((1, "paced"), (0, "ordered")):
                 opal.opal_set_pacing(mode)
                 for name, launch, moved in (("copy", lambda: opal.opal_copy(pa, pc, n, dt, stream), 2 * nbytes),
                                             ("add", lambda: opal.opal_add(pa, pb, pc, n, dt, stream), 3 * nbytes),

@@ -122,14 +122,13 @@ int opal_dot_static(const void* a, const void* b, size_t n, int dtype, double* r
  * the five kernels run as persistent wavefronts that issue their loads and stores in bursts on a
  * common timetable read off the chip-wide constant-rate counter, so that HBM sees one stream and
  * one direction at a time (2-3 % more bytes per second for the elementwise kernels, 3-4 % for
- * Dot, than workgroups handed out in index order; for Add and Triad the gain depends on how the
- * two input arrays lie relative to each other, and where they lie badly for it the library keeps
- * the index-ordered shape: opal_input_placement() below).  Results are the
+ * Dot, than workgroups handed out in index order; Add and Triad load their second input in the
+ * order that suits where the two inputs lie relative to each other, see csrc/launch_plan.hpp).  Results are the
  * same bits either way.  The timetable keeps a few device words of feedback inside the library's
  * device image (one copy per GPU); calls that overlap on one GPU share them, which can only cost
  * speed.  opal_set_pacing(0) switches to index-ordered workgroups for every size, 1 (the
  * default) uses the paced shapes from the sizes above on, 2 uses them for every array that holds at
- * least 16 chunks of the timetable, wherever its inputs lie (128 MiB for Copy and Mul; for measurements and tests).  The
+ * least 16 chunks of the timetable (128 MiB for Copy and Mul; for measurements and tests).  The
  * environment variable OPAL_PACING=0|1|2 sets the same before the first call; opal_get_pacing()
  * returns the current mode.  Process-wide, not per stream. */
 void opal_set_pacing(int mode);
@@ -175,15 +174,6 @@ const char* opal_status_string(int status);
 /* Name of the last HIP runtime error the calling thread met inside this library
  * ("hipSuccess" if none): the detail behind an OPAL_ERR_LAUNCH.  Static string. */
 const char* opal_last_hip_error(void);
-
-/* How the two input arrays of Add or Triad (or any two arrays read together) lie relative to
- * each other as far as the memory channels of an MI355X are concerned: the share of their 1 KiB
- * runs (256 sampled) whose two inputs fall into different channel classes, in 64ths (0..64; -1
- * for an unknown dtype or an impossible size).  0 is the best placement for large arrays (what arrays of 2^k bytes
- * carved back to back out of one allocation give), 64 the worst; up to 51 the library runs Add
- * and Triad on large arrays in the paced shape, beyond in the index-ordered one, which is the
- * faster of the two there.  Pure arithmetic on the two addresses: no GPU call, any pointers. */
-int opal_input_placement(const void* in0, const void* in1, size_t n, int dtype);
 
 /* Algorithmic bytes per element: every input read once and every output written
  * once (16/16/24/24/16 for fp64, half that for fp32).  kernel: 0 copy, 1 scale,

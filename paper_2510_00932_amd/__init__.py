@@ -17,7 +17,6 @@ from .binding import (  # noqa: F401
     load,
     opal_add,
     opal_bytes_per_element,
-    opal_input_placement,
     opal_copy,
     opal_dot,
     opal_dot_static,

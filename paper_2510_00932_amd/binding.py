@@ -80,8 +80,6 @@ def load():
     lib.opal_last_hip_error.restype = ctypes.c_char_p
     lib.opal_bytes_per_element.argtypes = [it, it]
     lib.opal_bytes_per_element.restype = sz
-    lib.opal_input_placement.argtypes = [vp, vp, sz, it]
-    lib.opal_input_placement.restype = it
     _LIB = lib
     return lib
 
@@ -135,11 +133,6 @@ def opal_status_string(status: int) -> str:
 
 def opal_bytes_per_element(kernel: int, dtype: int) -> int:
     return int(load().opal_bytes_per_element(int(kernel), int(dtype)))
-
-
-def opal_input_placement(in0, in1, n, dtype=None) -> int:
-    """Share of the runs (in 64ths) whose two inputs fall into different memory-channel classes (host arithmetic)."""
-    return int(load().opal_input_placement(_ptr(in0), _ptr(in1), n, _dtype_of(in0, dtype)))
 
 
 def opal_copy(a, c, n, dtype=None, stream=None):

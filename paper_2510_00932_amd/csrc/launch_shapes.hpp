@@ -43,15 +43,12 @@ constexpr unsigned kFinalBlock = 256;
 //
 // Placement.  Both elementwise shapes hand XCD x the 1 KiB runs whose index is x modulo 8, so an
 // XCD keeps reaching the same memory channels of an array.  For kernels with two inputs the
-// distance between the arrays then matters: the paced shape is at its best (86-88 % of the HBM
-// peak at 2 GiB per array) when the arrays are congruent modulo 16 KiB to within 3 KiB and
-// modulo 4 MiB to within 256 KiB, and at 81.5-83.5 % otherwise; the index-ordered shape behaves
-// the other way round (84-85 % where the arrays differ by 4-12 KiB modulo 16 KiB, 81-83 % where
-// they are congruent).  plan::placement_mismatch() turns the two input pointers into the share
-// of runs whose inputs fall into different channel classes; over 187 measured placements the
-// paced shape is ahead by 3.8 points where that share is 0, by 1.1 at one half, by 0.3 at 0.7, and
-// behind by 1.0-1.3 from 0.9 on, so Add and Triad take the index-ordered shape when more than
-// kPacedMaxMismatch / 64 of the sampled runs mismatch.
+// distance between the input arrays then matters (launch_plan.hpp: channel classes).  The paced
+// kernels load the runs of their second input in the order that matches the first input's
+// classes (plan::matched_run), which holds Add at 86-88 % of the HBM peak and Triad at 86-87.5 %
+// for nearly every distance; what remains are distances that differ in the lower two class bits
+// or by odd multiples of 1 MiB (Triad), at 81-85 %.  The index-ordered shape behaves the other way
+// round (84-85 % where the inputs differ by 4-12 KiB modulo 16 KiB, 81-83 % where they agree).
 struct PacedShape {
   unsigned waves;          // persistent wavefronts (8 or 4 per compute unit)
   unsigned k;              // 1 KiB runs per wavefront per burst
@@ -69,7 +66,6 @@ struct PacedShape {
 // what differs between settings is mostly how many launches have one XCD fall behind the
 // timetable (such a launch is 5-20 % slow), not the speed of a good launch.
 constexpr unsigned kPacedCUs = 256;             // the timetable is for this chip only
-constexpr unsigned kPacedMaxMismatch = 51;      // on plan::placement_mismatch's scale of 64 (0.8)
 constexpr int kPacedK1 = 8;                     // one-input kernels (copy, scale): K
 constexpr int kPacedK2 = 4;                     // two-input kernels (add, triad): K
 constexpr int kPacedKDot = 8;

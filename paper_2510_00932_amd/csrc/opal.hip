@@ -137,15 +137,6 @@ bool use_paced(size_t n, const DeviceInfo* dev, const PacedShape& sh) {
   return n / ((size_t)(sh.waves / 2) * sh.k * (1024 / sizeof(T))) >= 16;   // at least 16 chunks
 }
 
-// Kernels with two inputs: the paced shape only where the inputs lie suitably relative to each
-// other (launch_shapes.hpp); elsewhere the index-ordered shape is the faster one.
-template <typename T>
-bool inputs_suit_paced(const T* in0, const T* in1, size_t n) {
-  const size_t runs = n * sizeof(T) / plan::kBodyAlignBytes;
-  return plan::placement_mismatch(reinterpret_cast<uintptr_t>(in0), reinterpret_cast<uintptr_t>(in1), runs) <=
-         kPacedMaxMismatch;
-}
-
 int check_ptr(const void* p, size_t n, size_t elem) {
   if (n == 0) return OPAL_OK;
   if (p == nullptr) return OPAL_ERR_NULL;
@@ -202,8 +193,7 @@ int launch_stream(T* out, const T* in0, const T* in1, T s, size_t n, hipStream_t
   const PacedShape sh = g_shapes[kTwoInputs<OP> ? 1 : 0];
   if (pacing_mode() != 0) {
     const DeviceInfo* dev = device_info();
-    if (use_paced<T>(n, dev, sh) && (!kTwoInputs<OP> || pacing_mode() == 2 || inputs_suit_paced<T>(in0, in1, n)))
-      return launch_paced<T, OP>(out, in0, in1, s, n, *dev, sh, stream);
+    if (use_paced<T>(n, dev, sh)) return launch_paced<T, OP>(out, in0, in1, s, n, *dev, sh, stream);
   }
   return launch_stream_shape<T, OP, kStreamBlock, true>(out, in0, in1, s, n, stream);
 }
@@ -414,14 +404,6 @@ const char* opal_status_string(int status) {
 }
 
 const char* opal_last_hip_error(void) { return hipGetErrorName(g_last_hip_error); }
-
-int opal_input_placement(const void* in0, const void* in1, size_t n, int dtype) {
-  if (dtype != OPAL_F64 && dtype != OPAL_F32) return -1;
-  const size_t elem = dtype == OPAL_F64 ? 8 : 4;
-  if (n > (~(size_t)0 >> 1) / elem) return -1;
-  return (int)plan::placement_mismatch(reinterpret_cast<uintptr_t>(in0), reinterpret_cast<uintptr_t>(in1),
-                                       n * elem / plan::kBodyAlignBytes);
-}
 
 size_t opal_bytes_per_element(int kernel, int dtype) {
   if (dtype != OPAL_F64 && dtype != OPAL_F32) return 0;

@@ -179,6 +179,10 @@ __global__ __launch_bounds__(BLOCK) void stream_kernel(
 
 // Paced elementwise kernel: gridDim.x = p.waves one-wavefront workgroups (see the file header).
 // Same pointer and alignment conventions as stream_kernel; all accesses non-temporal.
+// Kernels with two inputs load the runs of the second input in the order in which their memory-channel
+// classes match those of the first (plan::matched_run), keep them in the registers of the slot they
+// were issued in, and store in slot order, picking the first input's run that belongs to each slot:
+// the data of a slot can be stored as soon as its second-input load has arrived, as without the matching.
 template <typename T, Op OP, int K, bool ALIGNED>
 __device__ __forceinline__ void paced_stream_body(
     T* __restrict__ out, const T* __restrict__ in0, const T* __restrict__ in1, T s, const plan::Paced& p,
@@ -198,7 +202,10 @@ __device__ __forceinline__ void paced_stream_body(
   PaceState st{};
   if (pace.period) st = pace_begin(pace, set);
   for (size_t chunk = set; chunk < p.nchunks; chunk += 2) {
-    V x[K], y[K];
+    V x[K], y[K];      // x[k]: run k of the first input; y[k]: the run of the second input issued in slot k
+    unsigned order[K];  // which run that is (wave-uniform)
+#pragma unroll
+    for (int k = 0; k < K; ++k) order[k] = (unsigned)k;
     uint32_t turn = 0;
     unsigned long long word = 0;
     if (pace.period) {
@@ -214,9 +221,18 @@ __device__ __forceinline__ void paced_stream_body(
     }
     if constexpr (kTwoInputs<OP>) {
       if (pace.period && pace.second_input) pace_wait_until(turn + pace.second_input);
+      if constexpr (K == (int)plan::kMatchedRuns) {
+        if (p.matched) {
+          const size_t r0 = wave_uniform(plan::paced_run(p, chunk, index, 0u) * RUN);
+          const uintptr_t a0 = reinterpret_cast<uintptr_t>(xbody + r0), a1 = reinterpret_cast<uintptr_t>(ybody + r0);
+#pragma unroll
+          for (int k = 0; k < K; ++k)
+            order[k] = (unsigned)__builtin_amdgcn_readfirstlane((int)plan::matched_run(a0, a1, (unsigned)k));
+        }
+      }
 #pragma unroll
       for (int k = 0; k < K; ++k) {
-        const size_t e0 = wave_uniform(plan::paced_run(p, chunk, index, (unsigned)k) * RUN);
+        const size_t e0 = wave_uniform(plan::paced_run(p, chunk, index, order[k]) * RUN);
         if (pace.gap && k) pace_wait_until(turn + pace.second_input + (uint32_t)k * pace.gap);
         y[k] = load16<T, ALIGNED, true>(ybody + e0 + e);
       }
@@ -234,9 +250,16 @@ __device__ __forceinline__ void paced_stream_body(
     }
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-      const size_t e0 = wave_uniform(plan::paced_run(p, chunk, index, (unsigned)k) * RUN);
+      const size_t e0 = wave_uniform(plan::paced_run(p, chunk, index, order[k]) * RUN);
       if (pace.gap && pace.store && k) pace_wait_until(turn + pace.store + (uint32_t)k * pace.gap);
-      store16<T, true>(obody + e0 + e, apply<OP, V>(x[k], y[k], (V)(s)));
+      V xs = x[k];
+      if constexpr (kTwoInputs<OP>) {
+        // the first input's run that belongs to this slot (all of them arrived before the second burst's)
+        xs = x[0];
+#pragma unroll
+        for (int j = 1; j < K; ++j) xs = (order[k] == (unsigned)j) ? x[j] : xs;
+      }
+      store16<T, true>(obody + e0 + e, apply<OP, V>(xs, y[k], (V)(s)));
     }
   }
 

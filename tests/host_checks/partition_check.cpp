@@ -86,6 +86,33 @@ static void replay_paced(uintptr_t addr, size_t n, unsigned elem, unsigned waves
   }
 }
 
+// The order in which a two-input paced kernel loads its second input and stores (matched_run): for
+// every wavefront and chunk the K slots must name every run 0..K-1 once, and, where adding a slot's
+// stride stays inside address bits 20-21, the run named for slot k must share the upper two class
+// bits of the first input's run k.
+static void check_matched(uintptr_t in0, uintptr_t in1, size_t chunks) {
+  const size_t stride = (size_t)1 << kMatchedStrideShift;
+  for (size_t chunk = 0; chunk < chunks; ++chunk)
+    for (unsigned index = 0; index < 1024; index += 37) {
+      const uintptr_t a0 = in0 + chunk * kMatchedRuns * stride + (uintptr_t)index * kBodyAlignBytes;
+      const uintptr_t a1 = in1 + chunk * kMatchedRuns * stride + (uintptr_t)index * kBodyAlignBytes;
+      unsigned seen = 0;
+      for (unsigned k = 0; k < kMatchedRuns; ++k) {
+        const unsigned kk = matched_run(a0, a1, k);
+        EXPECT(kk < kMatchedRuns, "matched_run out of range: %u", kk);
+        seen |= 1u << kk;
+        // class equality as far as the model goes: compare on addresses whose bits 20-21 hold the slot numbers
+        // themselves (no carry out of the field), all other bits as in a0 / a1
+        const uintptr_t field = (uintptr_t)3 << kMatchedStrideShift;
+        const uintptr_t x0 = (a0 & ~field) | ((((a0 >> kMatchedStrideShift) + k) & 3u) << kMatchedStrideShift);
+        const uintptr_t x1 = (a1 & ~field) | ((((a1 >> kMatchedStrideShift) + kk) & 3u) << kMatchedStrideShift);
+        EXPECT(((channel_class(x0) ^ channel_class(x1)) & 0xCu) == 0u, "classes differ: a0 %zx a1 %zx k %u kk %u",
+               (size_t)a0, (size_t)a1, k, kk);
+      }
+      EXPECT(seen == (1u << kMatchedRuns) - 1u, "not a permutation: a0 %zx a1 %zx", (size_t)a0, (size_t)a1);
+    }
+}
+
 // dot_partial_kernel (tiled).
 static void replay_tiled(uintptr_t addr, size_t n, unsigned elem, unsigned block, unsigned unroll, unsigned max_groups,
                          Cover& c) {
@@ -228,6 +255,21 @@ int main() {
     const Split sp = split(0x1000, n, 8);
     EXPECT(segment_count(sp, 64) == (sp.nvec + segment_vectors(64) - 1) / segment_vectors(64), "segment count");
     EXPECT(segment_count(sp, 64) > 1, "2^33 fp64 elements need more than one launch");
+  }
+  // matched order of the second input: aligned and misaligned pairs of arrays, distances with every class bit
+  {
+    const uintptr_t base = (uintptr_t)0x7f42ull << 32;
+    const uintptr_t distances[] = {0, 4096, 8192, 12288, 1024, 3072, 15360, (uintptr_t)1 << 20, (uintptr_t)2 << 20, (uintptr_t)3 << 20,
+                                   ((uintptr_t)1 << 20) + 4096, ((uintptr_t)2 << 20) + 8192, (uintptr_t)256 << 20,
+                                   ((uintptr_t)256 << 20) + 8192, (uintptr_t)2400001280u, 8, 4104, (uintptr_t)0x123456789};
+    for (uintptr_t d : distances) {
+      check_matched(base, base + ((uintptr_t)1 << 31) + d, 96);
+      check_matched(base + 8 + d, base, 96);
+      ++cases;
+    }
+    const Split whole{0u, (size_t)1 << 27, 0u};
+    EXPECT(paced(whole, 2048, 4, 3).matched, "the two-input shape in use is matched");
+    EXPECT(!paced(whole, 2048, 8, 3).matched && !paced(whole, 1024, 4, 3).matched, "other shapes are not");
   }
   if (g_failures) {
     std::printf("partition check: %d failure(s)\n", g_failures);
