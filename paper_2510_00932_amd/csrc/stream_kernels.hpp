@@ -36,9 +36,12 @@
 //   stores in one burst.  When a burst is issued is decided by a timetable on the chip-wide
 //   constant-rate counter (pacing.hpp), so that HBM sees the load burst of one set, then the
 //   store burst of the other, and so on: one stream and one direction at a time.  Measured on
-//   MI355X at n = 2^28 fp64 this moves 1.5-2 % more bytes per second than the dispatcher-ordered
-//   shape (dot: 4 %).  The rest (less than a chunk, a ragged run, head and tail scalars) is
-//   moved after the timetable part, unpaced, by all wavefronts together.
+//   MI355X at n = 2^28 fp64 this moves 2-3 % more bytes per second than the dispatcher-ordered
+//   shape (dot: 3-4 %).  Kernels with two inputs issue the loads of the second one in the order
+//   in which their memory-channel classes match the first one's (launch_plan.hpp), which keeps
+//   that gain wherever the two arrays lie relative to each other.  The rest (less than a chunk,
+//   a ragged run, head and tail scalars) is moved after the timetable part, unpaced, by all
+//   wavefronts together.
 //
 // Dot on arrays that fit the caches: tiled, a few workgroups per compute unit
 //   The body is cut into tiles of blockDim.x * U vectors; workgroup g takes
