@@ -232,7 +232,9 @@ def placement_scan(args):
     """How the two launch shapes of the elementwise kernels depend on where the three arrays lie relative to each
     other.  The arrays (2^28 fp64 by default, random values: zero-filled arrays hide the effect) are carved out of
     one allocation at base + k * (array bytes + skew), k = 0, 1, 2, for a list of skews; copy (a -> c), add and triad
-    are timed with the paced shapes on and off (average of `--steps` launches each, percent of the HBM peak).
+    are timed with the paced shapes on, on with the matched order of the second input starting from the opposite
+    assumption about the address bits above a page, on without the matched order, and off (average of `--steps`
+    launches each, percent of the HBM peak).
     Prints one JSON line."""
     import torch
 
@@ -267,13 +269,14 @@ def placement_scan(args):
             torch.cuda.synchronize()
             pa, pb, pc = a.data_ptr(), b.data_ptr(), c.data_ptr()
             row = {"skew_bytes": skew}
-            for mode, label in ((1, "paced"), (0, "ordered")):
+            for mode, label in ((1, "paced"), (1, "paced_other_start"), (1, "paced_same_order"), (0, "ordered")):
                 opal.opal_set_pacing(mode)
+                opal.opal_set_matched_order({"paced_same_order": 0, "paced_other_start": 2}.get(label, 1))
                 for name, launch, moved in (("copy", lambda: opal.opal_copy(pa, pc, n, dt, stream), 2 * nbytes),
                                             ("add", lambda: opal.opal_add(pa, pb, pc, n, dt, stream), 3 * nbytes),
                                             ("triad", lambda: opal.opal_triad(pa, pb, pc, wl.s, n, dt, stream), 3 * nbytes)):
-                    launch()
-                    launch()
+                    for _ in range(4):   # the launches in which the library times both orders of the second input
+                        launch()
                     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
                     for e0, e1 in ev:
                         e0.record(stream)
@@ -286,6 +289,7 @@ def placement_scan(args):
             print("bench.py: skew %d done" % skew, file=sys.stderr, flush=True)
     finally:
         opal.opal_set_pacing(mode0)
+        opal.opal_set_matched_order(True)
     print(json.dumps({"metric": "percent of the HBM peak against the relative placement of the arrays, 1 GPU", "unit": "%",
                       "config": {"workload": wl.name, "n": n}, "dtype": wl.dtype, "data": "synthetic",
                       "launches_per_figure": steps, "results": rows}))

@@ -134,6 +134,26 @@ int opal_dot_static(const void* a, const void* b, size_t n, int dtype, double* r
 void opal_set_pacing(int mode);
 int opal_get_pacing(void);
 
+/* The order in which the paced Add and Triad load the runs of their second input.  By default it is one of
+ * two orders that match the first input's memory-channel classes (csrc/launch_plan.hpp, matched_run); which
+ * of the two suits a pair of arrays depends on address bits a kernel cannot see, so the kernels time
+ * themselves: of every 128 launches with the same two inputs and n, the first four alternate between the
+ * two orders and the others use the faster one (csrc/pacing.hpp).  What was learnt lives in a few device
+ * words inside the library's device image (one copy per GPU, 64 pairs; pairs that collide, and calls that
+ * overlap on one GPU, learn nothing or the wrong order: slower, same results).
+ * opal_set_matched_order: 0 loads the second input in the same order as the first (no matching), 2 times
+ * the other of the two orders first, any other value restores the default; every call starts the learning
+ * afresh.  For measurements and tests; same results whatever the value; process-wide, call it while no
+ * other thread is inside the library.
+ * opal_matched_order_state: what has been learnt for the pair of inputs a paced Add or Triad call with these
+ * arguments would use (out: the call's output array; host pointer state[4] receives: launches so far, the
+ * shortest duration in ticks of the 100 MHz counter with order 0 and with order 1 (0xFFFFFFFF: none yet),
+ * the order the next launch will use).  Synchronous: it copies from the device and so waits for the work
+ * queued before it.  For tests and diagnosis.  Errors: OPAL_ERR_DTYPE, OPAL_ERR_NULL, OPAL_ERR_LAUNCH. */
+void opal_set_matched_order(int on);
+int opal_matched_order_state(const void* out, const void* in0, const void* in1, size_t n, int dtype,
+                             unsigned state[4]);
+
 /* Tuning hook for the timetable of one kind of paced kernel (0: Copy and Mul, 1: Add and Triad,
  * 2: Dot): the rate the timetable asks of memory in TB/s (1 TB = 1e12 B), where in the period the
  * store burst goes (fraction in [0,1); 0 = as soon as the data has arrived), for Dot how long

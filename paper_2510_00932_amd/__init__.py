@@ -25,6 +25,8 @@ from .binding import (  # noqa: F401
     opal_get_pacing,
     opal_pacing_configure,
     opal_set_pacing,
+    opal_set_matched_order,
+    opal_matched_order_state,
     opal_lds_stream,
     opal_lds_tile_elements,
     opal_scale,

@@ -64,6 +64,10 @@ def load():
     lib.opal_dot_static_scratch_bytes.restype = sz
     lib.opal_set_pacing.argtypes = [it]
     lib.opal_set_pacing.restype = None
+    lib.opal_set_matched_order.argtypes = [it]
+    lib.opal_set_matched_order.restype = None
+    lib.opal_matched_order_state.argtypes = [vp, vp, vp, sz, it, ctypes.POINTER(ctypes.c_uint)]
+    lib.opal_matched_order_state.restype = it
     lib.opal_get_pacing.argtypes = []
     lib.opal_get_pacing.restype = it
     lib.opal_pacing_configure.argtypes = [it, dbl, dbl, dbl, dbl, ctypes.c_uint, it, ctypes.c_uint]
@@ -177,6 +181,22 @@ def opal_dot_static(a, b, n, dtype, result, stream=None):
 def opal_set_pacing(mode) -> None:
     """0 / False: off; 1 / True: on from the library's size thresholds; 2: on wherever the shape fits."""
     load().opal_set_pacing(int(mode))
+
+
+def opal_set_matched_order(on) -> None:
+    """Paced Add and Triad: second input in one of the two class-matched orders, learnt per pair of inputs (default),
+    in the first input's order (0), or learnt with the other of the two orders timed first (2).  Every call starts
+    the learning afresh."""
+    load().opal_set_matched_order(2 if on == 2 and on is not True else (1 if on else 0))
+
+
+def opal_matched_order_state(out, in0, in1, n, dtype):
+    """(launches so far, shortest ticks with order 0, with order 1, order of the next launch) for the inputs of a
+    paced Add or Triad call with these arguments.  Waits for the work queued before it."""
+    state = (ctypes.c_uint * 4)()
+    _check(load().opal_matched_order_state(ctypes.c_void_p(out), ctypes.c_void_p(in0), ctypes.c_void_p(in1),
+                                           ctypes.c_size_t(n), int(dtype), state))
+    return tuple(int(v) for v in state)
 
 
 def opal_get_pacing() -> int:

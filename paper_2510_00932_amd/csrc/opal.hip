@@ -42,10 +42,11 @@ bool launch(void (*kernel)(Params...), unsigned grid, unsigned block, hipStream_
   return hip_ok(pack(args...));
 }
 
-// Device words of the pacing feedback (pacing.hpp) and the scratch of opal_dot_static: file-scope
+// Device words of the pacing feedback and of the learnt matched orders (pacing.hpp) and the scratch of opal_dot_static: file-scope
 // device arrays, one copy per GPU, held until the process ends.  In host code an array's name is
 // only a stand-in; its device address comes from hipGetSymbolAddress, once per device.
 static __device__ __align__(256) unsigned long long pace_words[kFeedbackWords];
+static __device__ __align__(256) unsigned order_words[plan::kOrderWords];
 constexpr size_t kStaticScratchBytes = (size_t)kDotMaxGroups * sizeof(double);   // 64 KiB
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
@@ -56,6 +57,7 @@ struct DeviceInfo {
   unsigned ticks_per_us = 0;              // rate of the constant counter the timetable runs on
   bool paced = false;                     // the paced shapes were measured on this kind of device
   unsigned long long* feedback = nullptr; // device address of pace_words
+  unsigned* order_words = nullptr;        // device address of order_words
   double* scratch = nullptr;              // device address of scratch
 };
 
@@ -78,6 +80,8 @@ const DeviceInfo* device_info() {
   void* ptr = nullptr;
   if (hip_ok(hipGetSymbolAddress(&ptr, HIP_SYMBOL(pace_words)))) d.feedback = static_cast<unsigned long long*>(ptr);
   ptr = nullptr;
+  if (hip_ok(hipGetSymbolAddress(&ptr, HIP_SYMBOL(order_words)))) d.order_words = static_cast<unsigned*>(ptr);
+  ptr = nullptr;
   if (hip_ok(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)))) d.scratch = static_cast<double*>(ptr);
   d.paced = gfx950 && d.cus == kPacedCUs && d.ticks_per_us > 0 && d.feedback != nullptr;
   if (!slot) {
@@ -95,6 +99,8 @@ const DeviceInfo* device_info() {
 
 // Run-time copies of the paced shapes (opal_pacing_configure may change the rates) and the switch.
 PacedShape g_shapes[3] = {kPacedOneInput, kPacedTwoInputs, kPacedDot};
+std::atomic<int> g_matched{1};   // two-input paced kernels: second input in class-matched order (plan::matched_run)
+std::atomic<unsigned> g_order_epoch{0};   // changes whenever the setting does: what was learnt before no longer applies
 std::atomic<int> g_pacing{-1};   // -1: not decided yet (environment), 0: off, 1: on, 2: on at every size the shape can hold
 
 int pacing_mode() {
@@ -118,6 +124,8 @@ Pace make_pace(const PacedShape& sh, unsigned streams, const DeviceInfo& dev) {
   pace.gap = (uint32_t)(sh.gap * pace.period);
   pace.tolerance = sh.tolerance;
   pace.feedback = sh.feedback ? dev.feedback : nullptr;
+  pace.order_words = dev.order_words;
+  pace.order_epoch = g_order_epoch.load(std::memory_order_relaxed);
   return pace;
 }
 
@@ -177,7 +185,10 @@ int launch_paced(T* out, const T* in0, const T* in1, T s, size_t n, const Device
   const plan::Split sp = plan::split(reinterpret_cast<uintptr_t>(out), n, sizeof(T));
   const bool aligned = aligned16_after(in0, sp.head, sizeof(T)) &&
                        (!kTwoInputs<OP> || aligned16_after(in1, sp.head, sizeof(T)));
-  const plan::Paced p = plan::paced(sp, sh.waves, K, sh.set_bit);
+  plan::Paced p = plan::paced(sp, sh.waves, K, sh.set_bit);
+  const int matched = g_matched.load(std::memory_order_relaxed);
+  p.matched = p.matched && matched != 0;
+  p.flip0 = matched == 2 ? 1u : 0u;
   const Pace pace = make_pace(sh, kTwoInputs<OP> ? 3u : 2u, dev);
   const bool ok = aligned ? launch(paced_stream_kernel<T, OP, K, true>, sh.waves, (unsigned)kWave, stream,
                                    out, in0, in1, s, p, pace)
@@ -350,6 +361,36 @@ int opal_dot_static(const void* a, const void* b, size_t n, int dtype, double* r
 }
 
 void opal_set_pacing(int mode) { g_pacing.store(mode <= 0 ? 0 : mode >= 2 ? 2 : 1, std::memory_order_relaxed); }
+
+int opal_matched_order_state(const void* out, const void* in0, const void* in1, size_t n, int dtype,
+                             unsigned state[4]) {
+  if (dtype != OPAL_F64 && dtype != OPAL_F32) return OPAL_ERR_DTYPE;
+  if (out == nullptr || in0 == nullptr || in1 == nullptr || state == nullptr) return OPAL_ERR_NULL;
+  const DeviceInfo* dev = device_info();
+  if (dev == nullptr || dev->order_words == nullptr) return OPAL_ERR_LAUNCH;
+  const size_t elem = dtype == OPAL_F64 ? 8 : 4;
+  const plan::Split sp = plan::split(reinterpret_cast<uintptr_t>(out), n, elem);   // as the kernels split
+  const plan::OrderKey key =
+      plan::order_key(reinterpret_cast<uintptr_t>(in0) + (uintptr_t)sp.head * elem,
+                      reinterpret_cast<uintptr_t>(in1) + (uintptr_t)sp.head * elem, sp.nvec,
+                      g_order_epoch.load(std::memory_order_relaxed));
+  unsigned words[plan::kOrderSlotWords];
+  if (!hip_ok(hipMemcpy(words, dev->order_words + (size_t)key.slot * plan::kOrderSlotWords, sizeof(words),
+                        hipMemcpyDeviceToHost)))
+    return OPAL_ERR_LAUNCH;
+  const bool known = words[0] == key.lo && words[1] == key.hi;
+  state[0] = known ? words[2] : 0u;
+  state[1] = known ? words[3] : 0xFFFFFFFFu;
+  state[2] = known ? words[4] : 0xFFFFFFFFu;
+  const unsigned first = g_matched.load(std::memory_order_relaxed) == 2 ? 1u : 0u;
+  state[3] = plan::order_of_launch(state[0], first, state[1], state[2]);
+  return OPAL_OK;
+}
+
+void opal_set_matched_order(int on) {
+  g_matched.store(on == 2 ? 2 : on != 0, std::memory_order_relaxed);
+  g_order_epoch.fetch_add(1u, std::memory_order_relaxed);
+}
 
 int opal_get_pacing(void) { return pacing_mode(); }
 

@@ -30,6 +30,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "launch_plan.hpp"
+
 namespace opal {
 
 constexpr unsigned kFeedbackCopies = 64;           // one per lane of a reporting wavefront
@@ -47,6 +49,8 @@ struct Pace {
   uint32_t gap;           // ticks between the accesses of one burst (0: all at once)
   uint32_t tolerance;     // lateness beyond which a reporter pushes the timetable back
   unsigned long long* feedback;   // kFeedbackWords device words, or nullptr (no feedback)
+  unsigned* order_words;          // plan::kOrderWords device words, or nullptr (matched order: nothing is learnt)
+  uint32_t order_epoch;           // part of the key under which an order is remembered: a new value starts afresh
 };
 
 __device__ __forceinline__ uint64_t pace_clock64() { return __builtin_amdgcn_s_memrealtime(); }
@@ -109,6 +113,61 @@ __device__ __forceinline__ unsigned long long pace_feedback_load(const Pace& p, 
   if (p.feedback == nullptr) return 0ull;
   return __hip_atomic_load(p.feedback + (size_t)(wave & (kFeedbackCopies - 1)) * kFeedbackStrideWords,
                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Which of the two matched orders (plan::matched_run, `flip`) suits a pair of input arrays is learnt
+// from the duration of whole launches, because nothing visible to a kernel tells it: the orders differ
+// by 4-5 % of a launch, launches of one order by a few tenths of a percent (one in ten by more, hence
+// the shortest of two).  A slot of device words (plan::order_key) holds for its pair the number of
+// launches so far and the shortest duration seen with each order in the current cycle of
+// plan::kOrderCycle launches; plan::order_of_launch() says which order a launch uses.  Every wavefront
+// reads the slot when it starts (an earlier kernel wrote it, so plain loads see it); the last
+// wavefront times itself, which is the launch's duration to within a period because the timetable
+// keeps all of them in step, and writes the slot when it is done.  Kernels that overlap on one GPU and
+// share a slot, or pairs whose keys fall into one slot, may learn nothing or the wrong order: that
+// costs speed, never correctness.
+struct OrderChoice {
+  unsigned* slot;      // nullptr: nothing is learnt
+  uint32_t key_lo, key_hi;
+  uint32_t launches;   // of this pair, before this one
+  uint32_t best[2];
+  uint32_t begin;
+  unsigned flip;       // this launch's order
+};
+
+__device__ __forceinline__ uint32_t order_uniform(uint32_t x) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)x); }
+
+__device__ __forceinline__ OrderChoice order_begin(const Pace& p, uintptr_t a0, uintptr_t a1, size_t n, unsigned first) {
+  OrderChoice c{};
+  if (p.order_words == nullptr) return c;
+  c.begin = pace_clock();
+  const plan::OrderKey key = plan::order_key(a0, a1, n, p.order_epoch);
+  c.key_lo = key.lo;
+  c.key_hi = key.hi;
+  c.slot = p.order_words + (size_t)key.slot * plan::kOrderSlotWords;
+  typedef uint32_t u4_t __attribute__((ext_vector_type(4)));
+  const u4_t w = *reinterpret_cast<const u4_t*>(c.slot);
+  const uint32_t w4 = c.slot[4];
+  const bool known = order_uniform(w.x) == c.key_lo && order_uniform(w.y) == c.key_hi;
+  c.launches = known ? order_uniform(w.z) : 0u;
+  c.best[0] = order_uniform(w.w);
+  c.best[1] = order_uniform(w4);
+  if (!known || c.launches % plan::kOrderCycle == 0u) c.best[0] = c.best[1] = 0xFFFFFFFFu;
+  c.flip = plan::order_of_launch(c.launches, first, c.best[0], c.best[1]);
+  return c;
+}
+
+// Call in one wavefront of the launch, when it has issued its last access.
+__device__ __forceinline__ void order_end(const OrderChoice& c) {
+  if (c.slot == nullptr || threadIdx.x != 0) return;
+  const uint32_t ticks = pace_clock() - c.begin;
+  uint32_t best[2] = {c.best[0], c.best[1]};
+  if (ticks < best[c.flip]) best[c.flip] = ticks;
+  c.slot[0] = c.key_lo;
+  c.slot[1] = c.key_hi;
+  c.slot[2] = c.launches + 1u;
+  c.slot[3] = best[0];
+  c.slot[4] = best[1];
 }
 
 // Adopt a published stretch if it belongs to this launch (stamps of one launch differ by at

@@ -202,6 +202,14 @@ __device__ __forceinline__ void paced_stream_body(
   const T* const ybody = kTwoInputs<OP> ? in1 + p.split.head : in0;
   const unsigned e = lane * L;
 
+  // Which of the two matched orders this launch uses (pacing.hpp: learnt per pair of input arrays).
+  OrderChoice choice{};
+  if constexpr (kTwoInputs<OP> && K == (int)plan::kMatchedRuns) {
+    if (p.matched && pace.period)
+      choice = order_begin(pace, reinterpret_cast<uintptr_t>(xbody), reinterpret_cast<uintptr_t>(ybody), p.split.nvec,
+                           p.flip0);
+  }
+  const unsigned flip = choice.slot != nullptr ? choice.flip : p.flip0;
   PaceState st{};
   if (pace.period) st = pace_begin(pace, set);
   for (size_t chunk = set; chunk < p.nchunks; chunk += 2) {
@@ -230,7 +238,7 @@ __device__ __forceinline__ void paced_stream_body(
           const uintptr_t a0 = reinterpret_cast<uintptr_t>(xbody + r0), a1 = reinterpret_cast<uintptr_t>(ybody + r0);
 #pragma unroll
           for (int k = 0; k < K; ++k)
-            order[k] = (unsigned)__builtin_amdgcn_readfirstlane((int)plan::matched_run(a0, a1, (unsigned)k));
+            order[k] = (unsigned)__builtin_amdgcn_readfirstlane((int)plan::matched_run(a0, a1, (unsigned)k, flip));
         }
       }
 #pragma unroll
@@ -276,7 +284,10 @@ __device__ __forceinline__ void paced_stream_body(
       store16<T, true>(obody + e0 + e, apply<OP, V>(x, y, (V)(s)));
     }
   }
-  if (wave == p.waves - 1) edge_elements<T, OP>(out, in0, in1, s, p.split, lane, kWave);
+  if (wave == p.waves - 1) {
+    edge_elements<T, OP>(out, in0, in1, s, p.split, lane, kWave);
+    order_end(choice);
+  }
 }
 
 template <typename T, Op OP, int K, bool ALIGNED>

@@ -110,6 +110,10 @@ static void check_matched(uintptr_t in0, uintptr_t in1, size_t chunks) {
                (size_t)a0, (size_t)a1, k, kk);
       }
       EXPECT(seen == (1u << kMatchedRuns) - 1u, "not a permutation: a0 %zx a1 %zx", (size_t)a0, (size_t)a1);
+      unsigned seen_flipped = 0;
+      for (unsigned k = 0; k < kMatchedRuns; ++k) seen_flipped |= 1u << matched_run(a0, a1, k, 1u);
+      EXPECT(seen_flipped == (1u << kMatchedRuns) - 1u, "not a permutation under the other assumption: a0 %zx a1 %zx",
+             (size_t)a0, (size_t)a1);
     }
 }
 
@@ -187,8 +191,41 @@ static void check_huge(uintptr_t addr, size_t n, unsigned elem) {
   EXPECT(tiled_ragged_group(t) < t.groups, "ragged group");
 }
 
+// Where a learnt order is remembered and which order a launch uses (order_key, order_of_launch).
+static void check_order_learning() {
+  unsigned used[kOrderSlots] = {0};
+  for (uintptr_t a0 = 0x7f0000000000ull; a0 < 0x7f0000000000ull + ((uintptr_t)64 << 21); a0 += (uintptr_t)1 << 21)
+    for (uintptr_t d : {(uintptr_t)1 << 31, ((uintptr_t)1 << 31) + 1024, (uintptr_t)3 << 30}) {
+      const OrderKey k = order_key(a0, a0 + d, (size_t)1 << 27, 0u);
+      EXPECT(k.hi != 0u && k.slot < kOrderSlots, "key %x %x slot %u", k.lo, k.hi, k.slot);
+      ++used[k.slot];
+      const OrderKey again = order_key(a0, a0 + d, (size_t)1 << 27, 0u);
+      EXPECT(again.lo == k.lo && again.hi == k.hi && again.slot == k.slot, "key not a function of its arguments");
+      const OrderKey swapped = order_key(a0 + d, a0, (size_t)1 << 27, 0u), other_n = order_key(a0, a0 + d, ((size_t)1 << 27) + 64, 0u),
+                     later = order_key(a0, a0 + d, (size_t)1 << 27, 1u);
+      EXPECT(swapped.lo != k.lo || swapped.hi != k.hi, "swapped inputs share a key");
+      EXPECT(other_n.lo != k.lo || other_n.hi != k.hi, "another n shares a key");
+      EXPECT(later.lo != k.lo || later.hi != k.hi, "another epoch shares a key");
+    }
+  unsigned most = 0, nonempty = 0;
+  for (unsigned u : used) { most = u > most ? u : most; nonempty += u != 0; }
+  EXPECT(nonempty >= kOrderSlots / 2 && most <= 12, "192 keys fall into %u slots, %u into one", nonempty, most);
+  for (unsigned first : {0u, 1u}) {
+    for (uint32_t cycle : {0u, kOrderCycle, 5u * kOrderCycle}) {
+      for (uint32_t i = 0; i < 4; ++i)
+        EXPECT(order_of_launch(cycle + i, first, 10u, 20u) == ((first ^ i) & 1u), "launch %u of a cycle, first %u", i, first);
+      for (uint32_t i = 4; i < kOrderCycle; i += 41) {
+        EXPECT(order_of_launch(cycle + i, first, 10u, 20u) == 0u, "faster order 0 not taken");
+        EXPECT(order_of_launch(cycle + i, first, 20u, 10u) == 1u, "faster order 1 not taken");
+        EXPECT(order_of_launch(cycle + i, first, 10u, 10u) == 0u, "tie");
+      }
+    }
+  }
+}
+
 int main() {
   size_t cases = 0;
+  check_order_learning();
   const size_t sizes[] = {0, 1, 2, 3, 4, 5, 7, 8, 15, 16, 17, 63, 64, 65, 127, 128, 129, 255, 256, 257, 511, 512, 513,
                           1023, 1024, 1025, 2047, 2048, 2049, 4095, 4096, 4097, 8191, 8193, 12289, 16385, 20000, 40961};
   for (unsigned elem : {8u, 4u})

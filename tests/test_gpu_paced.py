@@ -183,6 +183,61 @@ def test_overlapping_paced_calls_on_two_streams(pacing):
         assert abs(got - ref) <= 1e-12 * abs(ref), (j, got, ref)
 
 
+@pytest.mark.parametrize("setting", [0, 2])
+def test_every_order_of_the_second_input_gives_the_same_bits(parity, pacing, setting):
+    """The order in which a paced Add or Triad loads the runs of its second input (one of two orders matched to the
+    first input's memory-channel classes, tried in turn and then learnt; the first input's own order when switched
+    off) decides timing only.  The chain calls Add and Triad several times on the same arrays, so both matched
+    orders run."""
+    w = oi.workload(4)
+    n = _sizes(np.float64)[0]
+    arrays = [oi.uniform_array(w.seed, k, n, np.float64, w.lo, w.hi, threads=16) for k in range(3)]
+    try:
+        opal.opal_set_matched_order(setting)
+        parity.run_chain([x.copy() for x in arrays], w.s, (0, 1, 0), check_all_arrays_each_step=False)
+    finally:
+        opal.opal_set_matched_order(1)
+    parity.run_chain([x.copy() for x in arrays], w.s, (0, 1, 0), check_all_arrays_each_step=False)
+
+
+def test_the_faster_matched_order_is_learnt(pacing):
+    """Eight paced Add launches on the same arrays: the library has timed both matched orders twice and settled
+    for the faster one; told to time the other order first it settles for the same one (where the two differ by
+    more than launches of one order do), and other arrays start from nothing.  The sums are exact throughout."""
+    n = (1 << 27) + 4096
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(20251127)
+    a, b = (torch.rand(n, dtype=torch.float64, device=dev, generator=gen) + 0.5 for _ in range(2))
+    c = torch.empty(n, dtype=torch.float64, device=dev)
+    expect = a + b   # one rounding per element: the same bits as the oracle's sum
+    stream = torch.cuda.current_stream()
+    picks = []
+    try:
+        for first in (1, 2):
+            opal.opal_set_matched_order(first)
+            assert opal.opal_matched_order_state(c.data_ptr(), a.data_ptr(), b.data_ptr(), n, opal.OPAL_F64)[0] == 0
+            for launch in range(8):
+                c.zero_()
+                opal.opal_add(a.data_ptr(), b.data_ptr(), c.data_ptr(), n, opal.OPAL_F64, stream)
+                assert torch.equal(c, expect), "launch %d, setting %d" % (launch, first)
+                launches, best0, best1, nxt = opal.opal_matched_order_state(c.data_ptr(), a.data_ptr(), b.data_ptr(),
+                                                                            n, opal.OPAL_F64)
+                assert launches == launch + 1
+                if launch < 3:   # the first four launches alternate, starting with the order named first
+                    assert nxt == ((first - 1) ^ (launch + 1)) & 1
+            assert best0 != 0xFFFFFFFF and best1 != 0xFFFFFFFF
+            assert nxt == (1 if best1 < best0 else 0)
+            print("setting %d: shortest %d and %d ticks, order %d" % (first, best0, best1, nxt), flush=True)
+            picks.append((nxt, abs(best1 - best0) / min(best0, best1)))
+            # another pair of arrays has its own state
+            assert opal.opal_matched_order_state(c.data_ptr(), b.data_ptr(), a.data_ptr(), n, opal.OPAL_F64)[0] == 0
+        if all(gap > 0.025 for _, gap in picks):
+            assert picks[0][0] == picks[1][0]
+    finally:
+        opal.opal_set_matched_order(1)
+
+
 def test_pacing_configure_rejects_bad_values():
     for args in ((3, 7.0, 0.5, 0.0, 0.0, 100, 1), (-1, 7.0, 0.5, 0.0, 0.0, 100, 1), (0, 0.0, 0.5, 0.0, 0.0, 100, 1),
                  (0, 1e9, 0.5, 0.0, 0.0, 100, 1), (0, 7.0, 1.0, 0.0, 0.0, 100, 1), (0, 7.0, -0.1, 0.0, 0.0, 100, 1),
