@@ -157,6 +157,21 @@ def test_pacing_switch_and_tuning_hook_are_host_only():
     assert lib.opal_pacing_configure(0, 7.0, 0.5, 0.0, 0.0, 100, 1, 12) == 6
 
 
+def test_matched_order_state_argument_errors_are_found_on_the_host():
+    f64 = opal.OPAL_F64
+    assert _status(opal.opal_matched_order_state, A, A, A, 1 << 27, 7) == 2
+    assert _status(opal.opal_matched_order_state, 0, A, A, 1 << 27, f64) == 1
+    assert _status(opal.opal_matched_order_state, A, 0, A, 1 << 27, f64) == 1
+    assert _status(opal.opal_matched_order_state, A, A, 0, 1 << 27, f64) == 1
+    lib = opal.load()
+    assert lib.opal_matched_order_state(A, A, A, 1 << 27, f64, None) == 1
+    # without a GPU the device words cannot be reached: a runtime failure, not a crash
+    if _no_gpu():
+        assert _status(opal.opal_matched_order_state, A, A, A, 1 << 27, f64) == 5
+    for setting in (0, 2, 1):
+        opal.opal_set_matched_order(setting)   # host only
+
+
 def test_built_library_matches_the_sources():
     from paper_2510_00932_amd import build
     opal.load()
