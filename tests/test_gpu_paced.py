@@ -234,8 +234,43 @@ def test_the_faster_matched_order_is_learnt(pacing):
             assert opal.opal_matched_order_state(c.data_ptr(), b.data_ptr(), a.data_ptr(), n, opal.OPAL_F64)[0] == 0
         if all(gap > 0.025 for _, gap in picks):
             assert picks[0][0] == picks[1][0]
+        # after 128 launches both orders are timed afresh (setting 2 is still on: order 1 goes first)
+        for launch in range(8, 133):
+            expected_order = opal.opal_matched_order_state(c.data_ptr(), a.data_ptr(), b.data_ptr(), n, opal.OPAL_F64)[3]
+            if 128 <= launch < 132:
+                assert expected_order == (1 ^ (launch - 128)) & 1, launch
+            c.zero_()
+            opal.opal_add(a.data_ptr(), b.data_ptr(), c.data_ptr(), n, opal.OPAL_F64, stream)
+            if launch % 16 == 0 or launch >= 126:
+                assert torch.equal(c, expect), "launch %d" % launch
+        launches, best0, best1, nxt = opal.opal_matched_order_state(c.data_ptr(), a.data_ptr(), b.data_ptr(), n, opal.OPAL_F64)
+        assert launches == 133 and best0 != 0xFFFFFFFF and best1 != 0xFFFFFFFF and nxt == (1 if best1 < best0 else 0)
     finally:
         opal.opal_set_matched_order(1)
+
+
+@pytest.mark.parametrize("dtype", [torch.float64, torch.float32])
+def test_learning_the_order_keeps_triad_exact(pacing, dtype):
+    """Twelve paced Triad launches on the same arrays, fp64 and fp32: whichever order a launch uses, the result is
+    the two-rounding triad of the inputs, bit for bit (torch's own mul and add round once each)."""
+    n = (1 << 27) + 12345 if dtype == torch.float64 else (1 << 28) + 12345
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(7)
+    b, c = (torch.rand(n, dtype=dtype, device=dev, generator=gen) - 0.5 for _ in range(2))
+    a = torch.empty(n, dtype=dtype, device=dev)
+    s = -0.75
+    expect = torch.add(b, torch.mul(c, s))   # product rounded, then sum rounded
+    code = opal.OPAL_F64 if dtype == torch.float64 else opal.OPAL_F32
+    stream = torch.cuda.current_stream()
+    opal.opal_set_matched_order(1)
+    seen = set()
+    for launch in range(12):
+        seen.add(opal.opal_matched_order_state(a.data_ptr(), b.data_ptr(), c.data_ptr(), n, code)[3])
+        a.fill_(float("nan"))
+        opal.opal_triad(a.data_ptr(), b.data_ptr(), c.data_ptr(), s, n, code, stream)
+        assert torch.equal(a, expect), "launch %d" % launch
+    assert seen == {0, 1}
 
 
 def test_pacing_configure_rejects_bad_values():
