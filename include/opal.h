@@ -148,8 +148,9 @@ int opal_get_pacing(void);
  * opal_matched_order_state: what has been learnt for the pair of inputs a paced Add or Triad call with these
  * arguments would use (out: the call's output array; host pointer state[4] receives: launches so far, the
  * shortest duration in ticks of the 100 MHz counter with order 0 and with order 1 (0xFFFFFFFF: none yet),
- * the order the next launch will use).  Synchronous: it copies from the device and so waits for the work
- * queued before it.  For tests and diagnosis.  Errors: OPAL_ERR_DTYPE, OPAL_ERR_NULL, OPAL_ERR_LAUNCH. */
+ * the order the next launch will use).  Synchronous: it copies from the device with hipMemcpy, which waits
+ * for the work queued on the default stream only; synchronise any other stream the calls in question
+ * went to before asking.  For tests and diagnosis.  Errors: OPAL_ERR_DTYPE, OPAL_ERR_NULL, OPAL_ERR_LAUNCH. */
 void opal_set_matched_order(int on);
 int opal_matched_order_state(const void* out, const void* in0, const void* in1, size_t n, int dtype,
                              unsigned state[4]);

@@ -192,7 +192,7 @@ def opal_set_matched_order(on) -> None:
 
 def opal_matched_order_state(out, in0, in1, n, dtype):
     """(launches so far, shortest ticks with order 0, with order 1, order of the next launch) for the inputs of a
-    paced Add or Triad call with these arguments.  Waits for the work queued before it."""
+    paced Add or Triad call with these arguments.  Waits for the default stream only: synchronise other streams first."""
     state = (ctypes.c_uint * 4)()
     _check(load().opal_matched_order_state(ctypes.c_void_p(out), ctypes.c_void_p(in0), ctypes.c_void_p(in1),
                                            ctypes.c_size_t(n), int(dtype), state))
