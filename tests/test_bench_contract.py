@@ -47,3 +47,20 @@ def test_json_line_on_a_small_workload():
     assert d["cpu_baseline"]["kind"] == "oracle" and d["cpu_baseline"]["cores"] == 1
     assert d["check_vs_oracle"]["elementwise_bit_exact"] is True
     assert set(d["kernels"]) == {"copy", "scale", "add", "triad", "dot"}
+
+
+@pytest.mark.gpu
+def test_placement_scan_prints_every_setting():
+    """The scan's JSON line has, for every skew, the three kernels under all four settings and leaves the library's
+    switches as it found them (the scan runs in a process of its own, so only the line can be checked here)."""
+    p = subprocess.run([sys.executable, BENCH, "--placement-scan", "0,1024", "--steps", "3", "--n", str((1 << 26) + 4096)],
+                       capture_output=True, text=True, timeout=600)
+    assert p.returncode == 0, p.stderr[-2000:]
+    lines = [ln for ln in p.stdout.splitlines() if ln.strip()]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    assert [r["skew_bytes"] for r in d["results"]] == [0, 1024]
+    for r in d["results"]:
+        for kernel in ("copy", "add", "triad"):
+            for setting in ("paced", "paced_other_start", "paced_same_order", "ordered"):
+                assert 20.0 < r["%s_%s" % (kernel, setting)] < 100.0, (kernel, setting, r)
